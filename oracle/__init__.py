@@ -1,0 +1,221 @@
+"""ctypes access to the CPU oracle (``oracle/nfo.cpp``).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this module.
+It shares nothing with the GPU library: logical NCHW / OIHW numpy arrays in, numpy out.
+
+Paper: Eq. 1 (layer), Eq. 2 (auxiliary head), Eq. 3 (loss), Algorithm 2 (local step),
+and the activation cache between blocks.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnfo.so")
+_lib = None
+
+
+def build(verbose: bool = False) -> str:
+    """Compile ``nfo.cpp`` into ``libnfo.so`` next to it (g++, OpenMP)."""
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+           os.path.join(_HERE, "nfo.cpp"), "-o", _LIB_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return _LIB_PATH
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "C_in", "H_in", "W_in", "C_out", "R", "S", "stride", "pad",
+        "pool_kind", "pool_k", "pool_stride", "pool_pad",
+        "skip_kind", "skip_C", "skip_H", "skip_W", "skip_stride")]
+
+
+class AuxDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "C_in", "H_in", "W_in", "A", "R", "S", "pad", "relu", "pool_oh", "pool_ow", "n_classes")]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build()
+        _lib = C.CDLL(_LIB_PATH)
+        _lib.nfo_layer_dims.restype = C.c_int32
+        _lib.nfo_num_threads.restype = C.c_int32
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().nfo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    lib().nfo_set_num_threads(C.c_int32(n))
+
+
+def _suf(dtype) -> str:
+    dtype = np.dtype(dtype)
+    if dtype == np.float32:
+        return "f32"
+    if dtype == np.float64:
+        return "f64"
+    raise TypeError(f"oracle supports float32/float64, got {dtype}")
+
+
+def _p(a):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"], "oracle arrays must be C-contiguous"
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def layer_desc(C_in, H_in, W_in, C_out, R=3, S=3, stride=1, pad=1, pool_kind=0, pool_k=0,
+               pool_stride=0, pool_pad=0, skip_kind=0, skip_C=0, skip_H=0, skip_W=0,
+               skip_stride=0) -> LayerDesc:
+    return LayerDesc(C_in, H_in, W_in, C_out, R, S, stride, pad, pool_kind, pool_k, pool_stride,
+                     pool_pad, skip_kind, skip_C, skip_H, skip_W, skip_stride)
+
+
+def aux_desc(C_in, H_in, W_in, A, n_classes, R=3, S=3, pad=1, relu=1, pool_oh=2, pool_ow=2) -> AuxDesc:
+    return AuxDesc(C_in, H_in, W_in, A, R, S, pad, relu, pool_oh, pool_ow, n_classes)
+
+
+def layer_dims(d: LayerDesc):
+    """(Ho, Wo, Hp, Wp): conv output and emitted (post-pool) spatial sizes."""
+    o = [C.c_int32() for _ in range(4)]
+    rc = lib().nfo_layer_dims(C.byref(d), *[C.byref(v) for v in o])
+    if rc != 0:
+        raise ValueError("invalid layer descriptor")
+    return tuple(int(v.value) for v in o)
+
+
+def aux_out_hw(a: AuxDesc):
+    return a.H_in + 2 * a.pad - a.R + 1, a.W_in + 2 * a.pad - a.S + 1
+
+
+@dataclass
+class LayerFwd:
+    Z: np.ndarray
+    Y: np.ndarray
+    arg: np.ndarray | None
+
+
+def layer_fwd(d: LayerDesc, x, x_skip, W, b, Wp=None) -> LayerFwd:
+    """Eq. 1 for a batch ``x`` [B,C,H,W]."""
+    dt = x.dtype
+    B = x.shape[0]
+    Ho, Wo, Hp, Wp_ = layer_dims(d)
+    Z = np.empty((B, d.C_out, Ho, Wo), dt)
+    Y = np.empty((B, d.C_out, Hp, Wp_), dt)
+    arg = np.empty((B, d.C_out, Hp, Wp_), np.int32) if d.pool_kind else None
+    getattr(lib(), "nfo_layer_fwd_" + _suf(dt))(
+        C.byref(d), C.c_int32(B), _p(x), _p(x_skip), _p(W), _p(b), _p(Wp), _p(Z), _p(Y), _p(arg))
+    return LayerFwd(Z, Y, arg)
+
+
+@dataclass
+class AuxFwd:
+    U: np.ndarray
+    Pq: np.ndarray
+    z: np.ndarray
+    loss: float
+    dz: np.ndarray
+
+
+def aux_fwd_loss(a: AuxDesc, y, labels, Wa, ba, Wf, bf) -> AuxFwd:
+    """Eq. 2 and Eq. 3 (cross-entropy, batch mean) for the emitted activations ``y``."""
+    dt = y.dtype
+    B = y.shape[0]
+    Hu, Wu = aux_out_hw(a)
+    U = np.empty((B, a.A, Hu, Wu), dt)
+    Pq = np.empty((B, a.A * a.pool_oh * a.pool_ow), dt)
+    z = np.empty((B, a.n_classes), dt)
+    dz = np.empty((B, a.n_classes), dt)
+    loss = C.c_double()
+    labels = np.ascontiguousarray(labels, np.int32)
+    getattr(lib(), "nfo_aux_fwd_loss_" + _suf(dt))(
+        C.byref(a), C.c_int32(B), _p(y), _p(labels), _p(Wa), _p(ba), _p(Wf), _p(bf),
+        _p(U), _p(Pq), _p(z), C.byref(loss), _p(dz))
+    return AuxFwd(U, Pq, z, float(loss.value), dz)
+
+
+def local_bwd(d: LayerDesc, a: AuxDesc, x, x_skip, lf: LayerFwd, af: AuxFwd, Wa, Wf):
+    """Gradients of the local loss w.r.t. the layer's and the head's parameters only."""
+    dt = x.dtype
+    B = x.shape[0]
+    F = a.A * a.pool_oh * a.pool_ow
+    g = {
+        "W": np.empty((d.C_out, d.C_in, d.R, d.S), dt),
+        "b": np.empty((d.C_out,), dt),
+        "Wp": np.empty((d.C_out, d.skip_C), dt) if d.skip_kind == 2 else None,
+        "Wa": np.empty((a.A, a.C_in, a.R, a.S), dt),
+        "ba": np.empty((a.A,), dt),
+        "Wf": np.empty((a.n_classes, F), dt),
+        "bf": np.empty((a.n_classes,), dt),
+        "dY": np.empty_like(lf.Y),
+        "dZ": np.empty_like(lf.Z),
+    }
+    getattr(lib(), "nfo_local_bwd_" + _suf(dt))(
+        C.byref(d), C.byref(a), C.c_int32(B), _p(x), _p(x_skip), _p(lf.Z), _p(lf.Y), _p(lf.arg),
+        _p(af.U), _p(af.Pq), _p(af.dz), _p(Wa), _p(Wf),
+        _p(g["W"]), _p(g["b"]), _p(g["Wp"]), _p(g["Wa"]), _p(g["ba"]), _p(g["Wf"]), _p(g["bf"]),
+        _p(g["dY"]), _p(g["dZ"]))
+    return g
+
+
+def sgd_update(w, g, v, lr, mu) -> None:
+    """In place: v = mu*v + g; w = w - lr*v  (v None or mu == 0: w = w - lr*g)."""
+    getattr(lib(), "nfo_sgd_update_" + _suf(w.dtype))(
+        C.c_int64(w.size), _p(w), _p(g), _p(v), C.c_double(lr), C.c_double(mu))
+
+
+def cache_write(cache, cache_labels, first, y, labels) -> None:
+    B = y.shape[0]
+    se = int(np.prod(y.shape[1:]))
+    labels = None if labels is None else np.ascontiguousarray(labels, np.int32)
+    getattr(lib(), "nfo_cache_write_" + _suf(cache.dtype))(
+        _p(cache), _p(cache_labels), C.c_int64(se), C.c_int64(first), C.c_int32(B), _p(y), _p(labels))
+
+
+def cache_read(cache, cache_labels, first, idx, B, sample_shape):
+    se = int(np.prod(sample_shape))
+    x = np.empty((B,) + tuple(sample_shape), cache.dtype)
+    lab = np.empty((B,), np.int32) if cache_labels is not None else None
+    idx = None if idx is None else np.ascontiguousarray(idx, np.int64)
+    getattr(lib(), "nfo_cache_read_" + _suf(cache.dtype))(
+        _p(cache), _p(cache_labels), C.c_int64(se), C.c_int64(first), _p(idx), C.c_int32(B), _p(x), _p(lab))
+    return x, lab
+
+
+PARAM_NAMES = ("W", "b", "Wp", "Wa", "ba", "Wf", "bf")
+
+
+def local_step(d: LayerDesc, a: AuxDesc, x, x_skip, labels, params: dict, mom: dict | None,
+               lr: float, mu: float):
+    """One pass of the Algorithm 2 body.  ``params`` (and ``mom``) are updated in place.
+
+    Returns (Y emitted with the pre-update weights, loss, dict of gradients).
+    """
+    dt = x.dtype
+    B = x.shape[0]
+    _, _, Hp, Wp_ = layer_dims(d)
+    Y = np.empty((B, d.C_out, Hp, Wp_), dt)
+    grads = {k: (None if params.get(k) is None else np.empty_like(params[k])) for k in PARAM_NAMES}
+    loss = C.c_double()
+    labels = np.ascontiguousarray(labels, np.int32)
+    mom = mom or {}
+    getattr(lib(), "nfo_local_step_" + _suf(dt))(
+        C.byref(d), C.byref(a), C.c_int32(B), _p(x), _p(x_skip), _p(labels),
+        *[_p(params.get(k)) for k in PARAM_NAMES],
+        *[_p(grads[k]) for k in PARAM_NAMES],
+        *[_p(mom.get(k)) for k in PARAM_NAMES],
+        C.c_double(lr), C.c_double(mu), _p(Y), C.byref(loss))
+    return Y, float(loss.value), grads
