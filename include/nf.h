@@ -1,0 +1,152 @@
+/*
+ * nf — the per-layer local training step of adaptive local learning on one AMD MI355X
+ * (gfx950), as a C-ABI library of hand-written HIP kernels.
+ *
+ * Method: NeuroFlux (arXiv 2402.14139).  One local step is the body of Algorithm 2 for
+ * one (batch, layer) pair:
+ *     x_{n+1} = ReLU(P_n(theta_n * x_n))                         Eq. 1
+ *     z       = gamma_n F_n beta_n x_{n+1}                       Eq. 2
+ *     L       = mean_k CE(z_k, y_k)                              Eq. 3
+ *     gradients of L w.r.t. (theta_n, beta_n, gamma_n) only, then the update,
+ * plus the activation cache that carries a trained block's output to the next block at
+ * that block's own batch size (section "Efficient Forward Propagation via Prefetching and
+ * Adaptive Batching").
+ *
+ * ---- Data layout (all tensors dense fp32 unless stated, all pointers DEVICE pointers) ----
+ *   activations  NHWC : x[n][h][w][c]
+ *   conv weights KRSC : W[k][r][s][c]         (k = output channel)
+ *   projection        : Wp[k][c]              (1x1, stride skip_stride, no bias)
+ *   aux conv     ARSK : Wa[a][r][s][k]        (a = aux filter, k = layer output channel)
+ *   linear            : Wf[q][f], f = (i*pool_ow + j)*A + a   (NHWC flatten of the pooled map)
+ *   labels            : int32 in [0, n_classes)
+ *   cache row         : one sample's emitted activation, H*W*C contiguous floats (NHWC)
+ * These are index permutations of the paper-notation tensors (NCHW / OIHW / flatten a,i,j);
+ * the library never transposes activations.
+ *
+ * ---- Ownership, streams, errors -----------------------------------------------------------
+ *   The caller owns every buffer, including the workspace `ws` (size from
+ *   nf_workspace_bytes, 256-byte aligned).  The library allocates nothing and keeps no
+ *   state between calls.  `stream` is a hipStream_t passed as void* (NULL = default
+ *   stream); every call only enqueues work on it and never synchronises the host.
+ *   Every device pointer must be 16-byte aligned.
+ *   Every call returns NF_OK (0) or a negative nf_status.  Arguments are validated before
+ *   anything is enqueued, so a failing call has no side effects on device memory.
+ *   Labels outside [0,n_classes) and cache indices outside [0,capacity) are NOT detected
+ *   (they are data on the device); such a label contributes as if no class matched and
+ *   such an index is clamped into range.
+ *   Calls sharing a workspace must be ordered on one stream.
+ */
+#ifndef NF_H
+#define NF_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  NF_OK = 0,
+  NF_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  NF_ERR_BAD_DESC = -2,    /* non-positive size, inconsistent shapes, misaligned pointer   */
+  NF_ERR_UNSUPPORTED = -3, /* filter/stride/pool outside what the kernels implement        */
+  NF_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or smaller than required          */
+  NF_ERR_CACHE_RANGE = -5, /* first + B exceeds the cache capacity                         */
+  NF_ERR_DEVICE = -6       /* a HIP call failed (launch error)                             */
+} nf_status;
+
+/* Layer n of Eq. 1: conv theta_n (+bias, + optional shortcut), ReLU, optional max-pool P_n.
+ * Supported: R,S in {1,3,5,7}, stride in {1,2}, pad <= R/2 ... any pad < R; max-pool with
+ * 2*pool_pad <= pool_k <= 3, pool_stride in {1,2,3}. */
+typedef struct {
+  int32_t C_in, H_in, W_in;
+  int32_t C_out, R, S, stride, pad;
+  int32_t pool_kind; /* 0 none, 1 max */
+  int32_t pool_k, pool_stride, pool_pad;
+  int32_t skip_kind; /* 0 none; 1 identity (x_skip has the conv-output shape);
+                        2 projection: + sum_c Wp[k][c] * x_skip[n][i*skip_stride][j*skip_stride][c] */
+  int32_t skip_C, skip_H, skip_W, skip_stride;
+} nf_layer_desc;
+
+/* Auxiliary head A_n of Eq. 2: conv beta_n (R x S, stride 1, pad, + bias, ReLU if relu),
+ * adaptive average pool F_n to pool_oh x pool_ow, linear gamma_n to n_classes.
+ * C_in/H_in/W_in describe the tensor the layer emits (post-pool). */
+typedef struct {
+  int32_t C_in, H_in, W_in;
+  int32_t A, R, S, pad, relu;
+  int32_t pool_oh, pool_ow;
+  int32_t n_classes;
+} nf_aux_desc;
+
+typedef struct {
+  float lr, momentum;
+} nf_sgd_desc;
+
+/* Parameters of the layer (theta_n) and of its head (beta_n, gamma_n).  The same structs
+ * carry gradients and momentum buffers.  Wp is ignored unless skip_kind == 2. */
+typedef struct {
+  float *W, *b, *Wp;
+} nf_layer_params;
+typedef struct {
+  float *Wa, *ba, *Wf, *bf;
+} nf_aux_params;
+
+const char *nf_strerror(int32_t status);
+
+/* Emitted sizes: conv output (Ho,Wo) and post-pool (Hp,Wp).  Any out pointer may be NULL. */
+int32_t nf_layer_out_dims(const nf_layer_desc *d, int32_t *Ho, int32_t *Wo, int32_t *Hp, int32_t *Wp);
+
+/* Bytes of workspace the calls below need for this (layer, head, batch).  `a` may be NULL
+ * when only nf_layer_fwd will be called. */
+int32_t nf_workspace_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, size_t *out);
+
+/* Eq. 1.  x [B,H_in,W_in,C_in], x_skip per skip_kind (NULL if 0), y OUT [B,Hp,Wp,C_out].
+ * Records in ws what the backward needs (pool arg-max). */
+int32_t nf_layer_fwd(const nf_layer_desc *d, int32_t B, const float *x, const float *x_skip,
+                     const nf_layer_params *p, float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* Eq. 2 + Eq. 3.  y is the emitted activation [B,Hp,Wp,C_out]; *loss_out (device float)
+ * receives the batch-mean cross-entropy.  Leaves the head's activations and dL/dz in ws.
+ * `d` is the layer the head is attached to (it fixes where the head's data sits in ws). */
+int32_t nf_aux_fwd_loss(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *y,
+                        const int32_t *labels, const nf_aux_params *ap, float *loss_out, void *ws,
+                        size_t ws_bytes, void *stream);
+
+/* Algorithm 2, gradient line: gradients of the local loss w.r.t. theta_n, beta_n, gamma_n.
+ * Must follow nf_layer_fwd and nf_aux_fwd_loss on the same ws.  gp/ga are OVERWRITTEN
+ * (not accumulated).  No gradient is formed for x or x_skip. */
+int32_t nf_local_bwd_wgrad(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B,
+                           const float *x, const float *x_skip, const float *y,
+                           const nf_layer_params *p, const nf_aux_params *ap,
+                           const nf_layer_params *gp, const nf_aux_params *ga, void *ws,
+                           size_t ws_bytes, void *stream);
+
+/* Algorithm 2, update line, for n_tensors (<= 16) tensors in one launch:
+ *   v = momentum*v + g ; w = w - lr*v      (v == NULL or momentum == 0: w = w - lr*g)
+ * w, g, v are HOST arrays of device pointers; numel a HOST array of element counts. */
+int32_t nf_sgd_update(const nf_sgd_desc *s, int32_t n_tensors, float *const *w, const float *const *g,
+                      float *const *v, const int64_t *numel, void *stream);
+
+/* Activation cache.  cache [capacity][sample_elems], cache_labels [capacity] (may be NULL
+ * together with labels).  Write stores batch rows at [first, first+B).  Read gathers B rows:
+ * idx == NULL -> rows first..first+B-1, else rows idx[0..B) (device int64) — B is the
+ * CONSUMING block's batch size and need not equal the batch size used for writing. */
+int32_t nf_cache_write(float *cache, int32_t *cache_labels, int64_t capacity, int64_t sample_elems,
+                       int64_t first, int32_t B, const float *y, const int32_t *labels, void *stream);
+int32_t nf_cache_read(const float *cache, const int32_t *cache_labels, int64_t capacity,
+                      int64_t sample_elems, int64_t first, const int64_t *idx, int32_t B, float *x_out,
+                      int32_t *labels_out, void *stream);
+
+/* The whole Algorithm 2 body for one (batch, layer): forward, head, loss, gradients, update
+ * of p/ap in place, and y_out = the activation emitted with the PRE-update weights (it is
+ * the next layer's input).  gp/ga receive the gradients; vp/va are momentum buffers (may be
+ * NULL when s->momentum == 0). */
+int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd_desc *s, int32_t B,
+                      const float *x, const float *x_skip, const int32_t *labels,
+                      const nf_layer_params *p, const nf_aux_params *ap, const nf_layer_params *gp,
+                      const nf_aux_params *ga, const nf_layer_params *vp, const nf_aux_params *va,
+                      float *y_out, float *loss_out, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

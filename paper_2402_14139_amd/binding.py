@@ -1,0 +1,192 @@
+"""Thin ctypes binding over libnf.so (include/nf.h): argument marshalling only.
+
+Every step of the local training step runs in the library's HIP kernels; PyTorch is used
+for device memory (``torch.empty(..., device='cuda')``, ``data_ptr()``) and the current
+stream.  There is no CPU fallback: without the built library, or without a GPU, the compute
+calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnf.so")
+
+NF_OK = 0
+NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE_RANGE, NF_ERR_DEVICE = (
+    -1, -2, -3, -4, -5, -6)
+
+EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
+           "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step")
+
+
+class NfError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "C_in", "H_in", "W_in", "C_out", "R", "S", "stride", "pad",
+        "pool_kind", "pool_k", "pool_stride", "pool_pad",
+        "skip_kind", "skip_C", "skip_H", "skip_W", "skip_stride")]
+
+
+class AuxDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "C_in", "H_in", "W_in", "A", "R", "S", "pad", "relu", "pool_oh", "pool_ow", "n_classes")]
+
+
+class SgdDesc(C.Structure):
+    _fields_ = [("lr", C.c_float), ("momentum", C.c_float)]
+
+
+class LayerParams(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("b", C.c_void_p), ("Wp", C.c_void_p)]
+
+
+class AuxParams(C.Structure):
+    _fields_ = [("Wa", C.c_void_p), ("ba", C.c_void_p), ("Wf", C.c_void_p), ("bf", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libnf.so; raises if it has not been built (no fallback of any kind)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2402_14139_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        L.nf_strerror.restype = C.c_char_p
+        L.nf_strerror.argtypes = [C.c_int32]
+        for name in EXPORTS[1:]:
+            getattr(L, name).restype = C.c_int32
+        L.nf_layer_out_dims.argtypes = [C.POINTER(LayerDesc)] + [C.POINTER(C.c_int32)] * 4
+        L.nf_workspace_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.POINTER(C.c_size_t)]
+        L.nf_layer_fwd.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(LayerParams),
+                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_aux_fwd_loss.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.POINTER(AuxParams), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_local_bwd_wgrad.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.POINTER(LayerParams), C.POINTER(AuxParams),
+                                         C.POINTER(LayerParams), C.POINTER(AuxParams), C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
+        L.nf_sgd_update.argtypes = [C.POINTER(SgdDesc), C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                    C.POINTER(C.c_void_p), C.POINTER(C.c_int64), C.c_void_p]
+        L.nf_cache_write.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]
+        L.nf_cache_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p]
+        L.nf_local_step.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.POINTER(SgdDesc), C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.POINTER(LayerParams), C.POINTER(AuxParams), C.POINTER(LayerParams),
+                                    C.POINTER(AuxParams), C.POINTER(LayerParams), C.POINTER(AuxParams),
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().nf_strerror(int(status)).decode()
+
+
+def _check(rc, where):
+    if rc != NF_OK:
+        raise NfError(rc, where)
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or None / raw int passthrough)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def layer_params(W=None, b=None, Wp=None) -> LayerParams:
+    return LayerParams(_ptr(W), _ptr(b), _ptr(Wp))
+
+
+def aux_params(Wa=None, ba=None, Wf=None, bf=None) -> AuxParams:
+    return AuxParams(_ptr(Wa), _ptr(ba), _ptr(Wf), _ptr(bf))
+
+
+def nf_layer_out_dims(d: LayerDesc):
+    o = [C.c_int32() for _ in range(4)]
+    _check(lib().nf_layer_out_dims(C.byref(d), *[C.byref(v) for v in o]), "nf_layer_out_dims")
+    return tuple(int(v.value) for v in o)
+
+
+def nf_workspace_bytes(d: LayerDesc, a: AuxDesc | None, B: int) -> int:
+    out = C.c_size_t()
+    _check(lib().nf_workspace_bytes(C.byref(d), C.byref(a) if a is not None else None, B, C.byref(out)),
+           "nf_workspace_bytes")
+    return int(out.value)
+
+
+def _ws(ws):
+    return (_ptr(ws), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
+
+
+def nf_layer_fwd(d, B, x, x_skip, p: LayerParams, y, ws, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().nf_layer_fwd(C.byref(d), B, _ptr(x), _ptr(x_skip), C.byref(p), _ptr(y), wp, wn, _stream(stream)),
+           "nf_layer_fwd")
+
+
+def nf_aux_fwd_loss(d, a, B, y, labels, ap: AuxParams, loss_out, ws, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().nf_aux_fwd_loss(C.byref(d), C.byref(a), B, _ptr(y), _ptr(labels), C.byref(ap), _ptr(loss_out), wp,
+                                 wn, _stream(stream)), "nf_aux_fwd_loss")
+
+
+def nf_local_bwd_wgrad(d, a, B, x, x_skip, y, p, ap, gp, ga, ws, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().nf_local_bwd_wgrad(C.byref(d), C.byref(a), B, _ptr(x), _ptr(x_skip), _ptr(y), C.byref(p),
+                                    C.byref(ap), C.byref(gp), C.byref(ga), wp, wn, _stream(stream)),
+           "nf_local_bwd_wgrad")
+
+
+def nf_sgd_update(lr, momentum, w, g, v, stream=None):
+    """w, g, v: lists of torch tensors (v None when momentum == 0)."""
+    n = len(w)
+    s = SgdDesc(lr, momentum)
+    arr = lambda ts: (C.c_void_p * n)(*[_ptr(t) for t in ts])  # noqa: E731
+    numel = (C.c_int64 * n)(*[t.numel() for t in w])
+    _check(lib().nf_sgd_update(C.byref(s), n, arr(w), arr(g), arr(v) if v is not None else None, numel,
+                               _stream(stream)), "nf_sgd_update")
+
+
+def nf_cache_write(cache, cache_labels, capacity, sample_elems, first, B, y, labels, stream=None):
+    _check(lib().nf_cache_write(_ptr(cache), _ptr(cache_labels), capacity, sample_elems, first, B, _ptr(y),
+                                _ptr(labels), _stream(stream)), "nf_cache_write")
+
+
+def nf_cache_read(cache, cache_labels, capacity, sample_elems, first, idx, B, x_out, labels_out, stream=None):
+    _check(lib().nf_cache_read(_ptr(cache), _ptr(cache_labels), capacity, sample_elems, first, _ptr(idx), B,
+                               _ptr(x_out), _ptr(labels_out), _stream(stream)), "nf_cache_read")
+
+
+def nf_local_step(d, a, lr, momentum, B, x, x_skip, labels, p, ap, gp, ga, vp, va, y_out, loss_out, ws,
+                  stream=None):
+    s = SgdDesc(lr, momentum)
+    wp, wn = _ws(ws)
+    _check(lib().nf_local_step(C.byref(d), C.byref(a), C.byref(s), B, _ptr(x), _ptr(x_skip), _ptr(labels),
+                               C.byref(p), C.byref(ap), C.byref(gp), C.byref(ga),
+                               C.byref(vp) if vp is not None else None, C.byref(va) if va is not None else None,
+                               _ptr(y_out), _ptr(loss_out), wp, wn, _stream(stream)), "nf_local_step")

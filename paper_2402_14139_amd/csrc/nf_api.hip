@@ -1,0 +1,482 @@
+// C-ABI entry points of libnf (include/nf.h): argument validation, workspace layout and the
+// order in which the kernels of one local training step are enqueued (body of Algorithm 2,
+// NeuroFlux, arXiv 2402.14139).  No device work is enqueued before validation has passed.
+#include <cstdint>
+#include <cstring>
+
+#include "nf_internal.h"
+
+namespace nf {
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct LayerDims {
+  int Ho, Wo, Hp, Wp;
+};
+
+int32_t check_layer(const nf_layer_desc *d, LayerDims *o) {
+  if (!d) return NF_ERR_NULL;
+  if (d->C_in <= 0 || d->H_in <= 0 || d->W_in <= 0 || d->C_out <= 0 || d->R <= 0 || d->S <= 0 || d->stride <= 0 ||
+      d->pad < 0)
+    return NF_ERR_BAD_DESC;
+  if (d->R > 15 || d->S > 15 || d->stride > 4 || d->pad >= d->R + d->S) return NF_ERR_UNSUPPORTED;
+  const int hn = d->H_in + 2 * d->pad - d->R, wn = d->W_in + 2 * d->pad - d->S;
+  if (hn < 0 || wn < 0) return NF_ERR_BAD_DESC;
+  o->Ho = hn / d->stride + 1;
+  o->Wo = wn / d->stride + 1;
+  o->Hp = o->Ho;
+  o->Wp = o->Wo;
+  if (d->pool_kind != 0) {
+    if (d->pool_kind != 1) return NF_ERR_UNSUPPORTED;
+    if (d->pool_k <= 0 || d->pool_stride <= 0 || d->pool_pad < 0 || 2 * d->pool_pad > d->pool_k)
+      return NF_ERR_BAD_DESC;
+    if (d->pool_k > 15) return NF_ERR_UNSUPPORTED;
+    const int ph = o->Ho + 2 * d->pool_pad - d->pool_k, pw = o->Wo + 2 * d->pool_pad - d->pool_k;
+    if (ph < 0 || pw < 0) return NF_ERR_BAD_DESC;
+    o->Hp = ph / d->pool_stride + 1;
+    o->Wp = pw / d->pool_stride + 1;
+  }
+  if (d->skip_kind == 1) {
+    if (d->skip_C != d->C_out || d->skip_H != o->Ho || d->skip_W != o->Wo) return NF_ERR_BAD_DESC;
+  } else if (d->skip_kind == 2) {
+    if (d->skip_C <= 0 || d->skip_stride <= 0 || d->skip_H <= 0 || d->skip_W <= 0) return NF_ERR_BAD_DESC;
+    if ((long long)(o->Ho - 1) * d->skip_stride >= d->skip_H || (long long)(o->Wo - 1) * d->skip_stride >= d->skip_W)
+      return NF_ERR_BAD_DESC;
+  } else if (d->skip_kind != 0) {
+    return NF_ERR_BAD_DESC;
+  }
+  return NF_OK;
+}
+
+struct AuxDims {
+  int Hu, Wu, F;
+};
+
+int32_t check_aux(const nf_aux_desc *a, AuxDims *o) {
+  if (!a) return NF_ERR_NULL;
+  if (a->C_in <= 0 || a->H_in <= 0 || a->W_in <= 0 || a->A <= 0 || a->R <= 0 || a->S <= 0 || a->pad < 0 ||
+      a->pool_oh <= 0 || a->pool_ow <= 0 || a->n_classes <= 0)
+    return NF_ERR_BAD_DESC;
+  if (a->R != a->S || a->R > 15 || a->pad > a->R - 1) return NF_ERR_UNSUPPORTED;
+  o->Hu = a->H_in + 2 * a->pad - a->R + 1;
+  o->Wu = a->W_in + 2 * a->pad - a->S + 1;
+  if (o->Hu <= 0 || o->Wu <= 0) return NF_ERR_BAD_DESC;
+  const long long F = (long long)a->A * a->pool_oh * a->pool_ow;
+  if (F > 4096 || a->n_classes > 4096) return NF_ERR_UNSUPPORTED;
+  o->F = (int)F;
+  return NF_OK;
+}
+
+// every index the kernels form in 32-bit must fit
+int32_t check_sizes(const nf_layer_desc *d, const LayerDims &ld, int32_t B) {
+  if (B <= 0) return NF_ERR_BAD_DESC;
+  const long long lim = (1ll << 31) - 1;
+  const long long pix_in = (long long)B * d->H_in * d->W_in, pix_out = (long long)B * ld.Ho * ld.Wo;
+  const long long pix_skip = d->skip_kind == 2 ? (long long)B * d->skip_H * d->skip_W : 0;
+  if (pix_in > lim || pix_out > lim || pix_skip > lim) return NF_ERR_UNSUPPORTED;
+  if ((long long)d->R * d->S * d->C_in + d->skip_C > lim / 4) return NF_ERR_UNSUPPORTED;
+  if (B > 65535) return NF_ERR_UNSUPPORTED;
+  return NF_OK;
+}
+
+struct WsLayout {
+  size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, total;
+  int splits_aux, splits_layer, Qld_aux, Qld_layer;
+};
+
+WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B) {
+  WsLayout w;
+  std::memset(&w, 0, sizeof(w));
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += up(bytes);
+    return at;
+  };
+  const size_t f = sizeof(float);
+  const bool pooled = d->pool_kind != 0;
+  const size_t conv_out = (size_t)B * ld.Ho * ld.Wo * d->C_out, emitted = (size_t)B * ld.Hp * ld.Wp * d->C_out;
+  // pre-pool activation in the forward, dL/d(conv output) in the backward: never live together
+  w.T_dZ = take((pooled || a) ? conv_out * f : 0);
+  w.arg = take(pooled ? emitted : 0);
+  if (a) {
+    const size_t u = (size_t)B * ad.Hu * ad.Wu * a->A;
+    w.U = take(u * f);
+    w.Pq = take((size_t)B * ad.F * f);
+    w.dz = take((size_t)B * a->n_classes * f);
+    w.loss_n = take((size_t)B * f);
+    w.dPq = take((size_t)B * ad.F * f);
+    w.dU = take(u * f);
+    w.WaT = take((size_t)a->A * a->R * a->S * a->C_in * f);
+    w.dY = take(pooled ? emitted * f : 0);
+    const int Qa = a->R * a->S * a->C_in, Ql = d->R * d->S * d->C_in + (d->skip_kind == 2 ? d->skip_C : 0);
+    w.Qld_aux = (Qa + 3) / 4 * 4;
+    w.Qld_layer = (Ql + 3) / 4 * 4;
+    w.splits_aux = wgrad_pick_splits(a->A, Qa, B * ad.Hu * ad.Wu);
+    w.splits_layer = wgrad_pick_splits(d->C_out, Ql, B * ld.Ho * ld.Wo);
+    const size_t pa = (size_t)w.splits_aux * a->A * w.Qld_aux, pl = (size_t)w.splits_layer * d->C_out * w.Qld_layer;
+    w.part = take((pa > pl ? pa : pl) * f);
+    const size_t ba = (size_t)w.splits_aux * a->A, bl = (size_t)w.splits_layer * d->C_out;
+    w.part_b = take((ba > bl ? ba : bl) * f);
+  }
+  w.total = off ? off : ALIGN;
+  return w;
+}
+
+int32_t check_ws(const void *ws, size_t have, size_t need) {
+  if (!ws) return NF_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % ALIGN) return NF_ERR_WORKSPACE;
+  if (have < need) return NF_ERR_WORKSPACE;
+  return NF_OK;
+}
+
+inline float *wsf(void *ws, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(ws) + off); }
+
+#define NF_HIP(expr)                       \
+  do {                                     \
+    if ((expr) != hipSuccess) return NF_ERR_DEVICE; \
+  } while (0)
+
+// ---- enqueue helpers (arguments already validated) ----
+
+int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const float *x, const float *xs,
+                      const nf_layer_params *p, float *y, void *ws, const WsLayout &w, hipStream_t st) {
+  const bool pooled = d->pool_kind != 0;
+  FwdProblem f;
+  std::memset((void *)&f, 0, sizeof(f));
+  f.x = x, f.w = p->W, f.bias = p->b;
+  f.H = d->H_in, f.W = d->W_in, f.C = d->C_in, f.N = d->C_out, f.R = d->R, f.S = d->S, f.stride = d->stride,
+  f.pad = d->pad, f.Ho = ld.Ho, f.Wo = ld.Wo;
+  if (d->skip_kind == 1) f.addsrc = xs;
+  if (d->skip_kind == 2) f.xs = xs, f.wp = p->Wp, f.Cs = d->skip_C, f.Hs = d->skip_H, f.Ws = d->skip_W, f.ss = d->skip_stride;
+  f.relu = 1;
+  f.M = B * ld.Ho * ld.Wo, f.RSC = d->R * d->S * d->C_in, f.Kg = f.RSC + f.Cs;
+  f.div_howo = FastDiv(ld.Ho * ld.Wo), f.div_wo = FastDiv(ld.Wo);
+  f.out = pooled ? wsf(ws, w.T_dZ) : y;
+  NF_HIP(launch_igemm_fwd(f, st));
+  if (pooled)
+    NF_HIP(launch_maxpool_fwd(wsf(ws, w.T_dZ), y, reinterpret_cast<uint8_t *>(wsf(ws, w.arg)), B, ld.Ho, ld.Wo,
+                              d->C_out, ld.Hp, ld.Wp, d->pool_k, d->pool_stride, d->pool_pad, st));
+  return NF_OK;
+}
+
+HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
+  HeadShape h;
+  h.B = B, h.Hu = ad.Hu, h.Wu = ad.Wu, h.A = a->A, h.oh = a->pool_oh, h.ow = a->pool_ow, h.F = ad.F,
+  h.Cls = a->n_classes, h.relu = a->relu;
+  return h;
+}
+
+int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const int32_t *labels,
+                    const nf_aux_params *ap, float *loss_out, void *ws, const WsLayout &w, hipStream_t st) {
+  FwdProblem f;
+  std::memset((void *)&f, 0, sizeof(f));
+  f.x = y, f.w = ap->Wa, f.bias = ap->ba;
+  f.H = a->H_in, f.W = a->W_in, f.C = a->C_in, f.N = a->A, f.R = a->R, f.S = a->S, f.stride = 1, f.pad = a->pad,
+  f.Ho = ad.Hu, f.Wo = ad.Wu;
+  f.relu = a->relu ? 1 : 0;
+  f.M = B * ad.Hu * ad.Wu, f.RSC = a->R * a->S * a->C_in, f.Kg = f.RSC;
+  f.div_howo = FastDiv(ad.Hu * ad.Wu), f.div_wo = FastDiv(ad.Wu);
+  f.out = wsf(ws, w.U);
+  NF_HIP(launch_igemm_fwd(f, st));
+  NF_HIP(launch_head_fwd(head_shape(a, ad, B), wsf(ws, w.U), labels, ap->Wf, ap->bf, wsf(ws, w.Pq), wsf(ws, w.dz),
+                         wsf(ws, w.loss_n), loss_out, st));
+  return NF_OK;
+}
+
+int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B,
+                const float *x, const float *xs, const float *y, const nf_layer_params *p,
+                const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga, void *ws,
+                const WsLayout &w, hipStream_t st) {
+  (void)p;
+  const bool pooled = d->pool_kind != 0;
+  const HeadShape hs = head_shape(a, ad, B);
+  float *dU = wsf(ws, w.dU), *dZ = wsf(ws, w.T_dZ);
+  // gamma_n, then back through F_n and the aux ReLU
+  NF_HIP(launch_fc_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ap->Wf, ga->Wf, ga->bf, wsf(ws, w.dPq), st));
+  NF_HIP(launch_pool_relu_bwd(hs, wsf(ws, w.U), wsf(ws, w.dPq), dU, st));
+  // beta_n: weight + bias gradient
+  {
+    WgradProblem g;
+    std::memset((void *)&g, 0, sizeof(g));
+    g.d = dU, g.x = y, g.part = wsf(ws, w.part), g.part_b = wsf(ws, w.part_b);
+    g.H = a->H_in, g.W = a->W_in, g.C = a->C_in, g.R = a->R, g.S = a->S, g.stride = 1, g.pad = a->pad, g.Ho = ad.Hu,
+    g.Wo = ad.Wu;
+    g.P = a->A, g.M = B * ad.Hu * ad.Wu, g.RSC = a->R * a->S * a->C_in, g.Q = g.RSC, g.Qld = w.Qld_aux;
+    g.splits = w.splits_aux;
+    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;
+    g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);
+    NF_HIP(launch_igemm_wgrad(g, st));
+    NF_HIP(launch_wgrad_reduce(g.part, g.part_b, g.splits, g.P, g.Q, g.Qld, g.Q, ga->Wa, nullptr, ga->ba, st));
+  }
+  // beta_n: data gradient w.r.t. the emitted activation, layer ReLU mask fused when un-pooled
+  {
+    NF_HIP(launch_flip_transpose(ap->Wa, wsf(ws, w.WaT), a->A, a->R, a->S, a->C_in, st));
+    FwdProblem f;
+    std::memset((void *)&f, 0, sizeof(f));
+    f.x = dU, f.w = wsf(ws, w.WaT);
+    f.H = ad.Hu, f.W = ad.Wu, f.C = a->A, f.N = a->C_in, f.R = a->R, f.S = a->S, f.stride = 1,
+    f.pad = a->R - 1 - a->pad, f.Ho = a->H_in, f.Wo = a->W_in;
+    f.M = B * a->H_in * a->W_in, f.RSC = a->R * a->S * a->A, f.Kg = f.RSC;
+    f.div_howo = FastDiv(a->H_in * a->W_in), f.div_wo = FastDiv(a->W_in);
+    f.mask = pooled ? nullptr : y;
+    f.out = pooled ? wsf(ws, w.dY) : dZ;
+    NF_HIP(launch_igemm_fwd(f, st));
+    if (pooled)
+      NF_HIP(launch_maxpool_bwd(wsf(ws, w.dY), y, reinterpret_cast<const uint8_t *>(wsf(ws, w.arg)), dZ, B, ld.Ho,
+                                ld.Wo, d->C_out, ld.Hp, ld.Wp, d->pool_k, d->pool_stride, d->pool_pad, st));
+  }
+  // theta_n: weight, bias and projection gradients; nothing flows to x or x_skip
+  {
+    WgradProblem g;
+    std::memset((void *)&g, 0, sizeof(g));
+    g.d = dZ, g.x = x, g.part = wsf(ws, w.part), g.part_b = wsf(ws, w.part_b);
+    g.H = d->H_in, g.W = d->W_in, g.C = d->C_in, g.R = d->R, g.S = d->S, g.stride = d->stride, g.pad = d->pad,
+    g.Ho = ld.Ho, g.Wo = ld.Wo;
+    if (d->skip_kind == 2) g.xs = xs, g.Cs = d->skip_C, g.Hs = d->skip_H, g.Ws = d->skip_W, g.ss = d->skip_stride;
+    g.P = d->C_out, g.M = B * ld.Ho * ld.Wo, g.RSC = d->R * d->S * d->C_in, g.Q = g.RSC + g.Cs, g.Qld = w.Qld_layer;
+    g.splits = w.splits_layer;
+    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;
+    g.div_howo = FastDiv(ld.Ho * ld.Wo), g.div_wo = FastDiv(ld.Wo);
+    NF_HIP(launch_igemm_wgrad(g, st));
+    NF_HIP(launch_wgrad_reduce(g.part, g.part_b, g.splits, g.P, g.Q, g.Qld, g.RSC, gp->W, gp->Wp, gp->b, st));
+  }
+  return NF_OK;
+}
+
+int32_t check_layer_ptrs(const nf_layer_desc *d, const float *x, const float *xs, const nf_layer_params *p) {
+  if (!x || !p || !p->W || !p->b) return NF_ERR_NULL;
+  if (d->skip_kind != 0 && !xs) return NF_ERR_NULL;
+  if (d->skip_kind == 2 && !p->Wp) return NF_ERR_NULL;
+  if (!aligned16(x) || !aligned16(xs) || !aligned16(p->W) || !aligned16(p->b) ||
+      (d->skip_kind == 2 && !aligned16(p->Wp)))
+    return NF_ERR_BAD_DESC;
+  return NF_OK;
+}
+
+int32_t check_aux_ptrs(const nf_aux_params *ap) {
+  if (!ap || !ap->Wa || !ap->ba || !ap->Wf || !ap->bf) return NF_ERR_NULL;
+  if (!aligned16(ap->Wa) || !aligned16(ap->ba) || !aligned16(ap->Wf) || !aligned16(ap->bf)) return NF_ERR_BAD_DESC;
+  return NF_OK;
+}
+
+int32_t check_pair(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a) {
+  if (a->C_in != d->C_out || a->H_in != ld.Hp || a->W_in != ld.Wp) return NF_ERR_BAD_DESC;
+  return NF_OK;
+}
+
+int collect_sgd(const nf_layer_desc *d, const nf_aux_desc *a, const AuxDims &ad, const nf_layer_params *p,
+                const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga,
+                const nf_layer_params *vp, const nf_aux_params *va, SgdTensors *t) {
+  int n = 0;
+  auto add = [&](float *w, const float *g, float *v, long long numel) {
+    t->w[n] = w, t->g[n] = g, t->v[n] = v, t->numel[n] = numel;
+    ++n;
+  };
+  add(p->W, gp->W, vp ? vp->W : nullptr, (long long)d->C_out * d->R * d->S * d->C_in);
+  add(p->b, gp->b, vp ? vp->b : nullptr, d->C_out);
+  if (d->skip_kind == 2) add(p->Wp, gp->Wp, vp ? vp->Wp : nullptr, (long long)d->C_out * d->skip_C);
+  add(ap->Wa, ga->Wa, va ? va->Wa : nullptr, (long long)a->A * a->R * a->S * a->C_in);
+  add(ap->ba, ga->ba, va ? va->ba : nullptr, a->A);
+  add(ap->Wf, ga->Wf, va ? va->Wf : nullptr, (long long)a->n_classes * ad.F);
+  add(ap->bf, ga->bf, va ? va->bf : nullptr, a->n_classes);
+  return n;
+}
+
+}  // namespace
+}  // namespace nf
+
+using namespace nf;
+
+extern "C" {
+
+const char *nf_strerror(int32_t s) {
+  switch (s) {
+    case NF_OK: return "ok";
+    case NF_ERR_NULL: return "a required pointer is NULL";
+    case NF_ERR_BAD_DESC: return "bad descriptor (non-positive or inconsistent sizes, or misaligned pointer)";
+    case NF_ERR_UNSUPPORTED: return "configuration outside what the kernels implement";
+    case NF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case NF_ERR_CACHE_RANGE: return "cache range exceeds capacity";
+    case NF_ERR_DEVICE: return "HIP error while enqueueing";
+    default: return "unknown status";
+  }
+}
+
+int32_t nf_layer_out_dims(const nf_layer_desc *d, int32_t *Ho, int32_t *Wo, int32_t *Hp, int32_t *Wp) {
+  LayerDims ld;
+  const int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if (Ho) *Ho = ld.Ho;
+  if (Wo) *Wo = ld.Wo;
+  if (Hp) *Hp = ld.Hp;
+  if (Wp) *Wp = ld.Wp;
+  return NF_OK;
+}
+
+int32_t nf_workspace_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, size_t *out) {
+  if (!out) return NF_ERR_NULL;
+  LayerDims ld;
+  AuxDims ad = {0, 0, 0};
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if (a) {
+    if ((rc = check_aux(a, &ad))) return rc;
+    if ((rc = check_pair(d, ld, a))) return rc;
+  }
+  *out = ws_layout(d, ld, a, ad, B).total;
+  return NF_OK;
+}
+
+int32_t nf_layer_fwd(const nf_layer_desc *d, int32_t B, const float *x, const float *x_skip,
+                     const nf_layer_params *p, float *y, void *ws, size_t ws_bytes, void *stream) {
+  LayerDims ld;
+  AuxDims ad = {0, 0, 0};
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if ((rc = check_layer_ptrs(d, x, x_skip, p))) return rc;
+  if (!y) return NF_ERR_NULL;
+  if (!aligned16(y)) return NF_ERR_BAD_DESC;
+  // the layout with a head is a superset that starts with the same regions, so a workspace
+  // sized for the full step is accepted as well
+  const WsLayout w = ws_layout(d, ld, nullptr, ad, B);
+  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
+  return run_layer_fwd(d, ld, B, x, x_skip, p, y, ws, w, static_cast<hipStream_t>(stream));
+}
+
+int32_t nf_aux_fwd_loss(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *y,
+                        const int32_t *labels, const nf_aux_params *ap, float *loss_out, void *ws,
+                        size_t ws_bytes, void *stream) {
+  LayerDims ld;
+  AuxDims ad;
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_aux(a, &ad))) return rc;
+  if ((rc = check_pair(d, ld, a))) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if (!y || !labels || !loss_out) return NF_ERR_NULL;
+  if ((rc = check_aux_ptrs(ap))) return rc;
+  if (!aligned16(y)) return NF_ERR_BAD_DESC;
+  const WsLayout w = ws_layout(d, ld, a, ad, B);
+  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
+  return run_aux_fwd(a, ad, B, y, labels, ap, loss_out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+int32_t nf_local_bwd_wgrad(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *x,
+                           const float *x_skip, const float *y, const nf_layer_params *p,
+                           const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga,
+                           void *ws, size_t ws_bytes, void *stream) {
+  LayerDims ld;
+  AuxDims ad;
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_aux(a, &ad))) return rc;
+  if ((rc = check_pair(d, ld, a))) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if ((rc = check_layer_ptrs(d, x, x_skip, p))) return rc;
+  if ((rc = check_aux_ptrs(ap))) return rc;
+  if ((rc = check_layer_ptrs(d, x, x_skip, gp))) return rc;
+  if ((rc = check_aux_ptrs(ga))) return rc;
+  if (!y) return NF_ERR_NULL;
+  if (!aligned16(y)) return NF_ERR_BAD_DESC;
+  const WsLayout w = ws_layout(d, ld, a, ad, B);
+  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
+  return run_bwd(d, ld, a, ad, B, x, x_skip, y, p, ap, gp, ga, ws, w, static_cast<hipStream_t>(stream));
+}
+
+int32_t nf_sgd_update(const nf_sgd_desc *s, int32_t n_tensors, float *const *w, const float *const *g,
+                      float *const *v, const int64_t *numel, void *stream) {
+  if (!s || !w || !g || !numel) return NF_ERR_NULL;
+  if (n_tensors <= 0 || n_tensors > 16) return NF_ERR_BAD_DESC;
+  const bool use_v = s->momentum != 0.f;
+  if (use_v && !v) return NF_ERR_NULL;
+  SgdTensors t;
+  std::memset(&t, 0, sizeof(t));
+  for (int i = 0; i < n_tensors; ++i) {
+    if (!w[i] || !g[i] || (use_v && !v[i])) return NF_ERR_NULL;
+    if (numel[i] <= 0) return NF_ERR_BAD_DESC;
+    if (!aligned16(w[i]) || !aligned16(g[i]) || (use_v && !aligned16(v[i]))) return NF_ERR_BAD_DESC;
+    t.w[i] = w[i], t.g[i] = g[i], t.v[i] = use_v ? v[i] : nullptr, t.numel[i] = numel[i];
+  }
+  t.n = n_tensors, t.lr = s->lr, t.mu = s->momentum;
+  NF_HIP(launch_sgd(t, static_cast<hipStream_t>(stream)));
+  return NF_OK;
+}
+
+static int32_t check_cache(const void *cache, const void *clab, int64_t capacity, int64_t se, int64_t first,
+                           int32_t B, const void *buf, const void *lab) {
+  if (!cache || !buf) return NF_ERR_NULL;
+  if ((clab == nullptr) != (lab == nullptr)) return NF_ERR_NULL;
+  if (capacity <= 0 || se <= 0 || B <= 0 || B > 65535) return NF_ERR_BAD_DESC;
+  if (!aligned16(cache) || !aligned16(buf)) return NF_ERR_BAD_DESC;
+  if (first < 0 || first + B > capacity) return NF_ERR_CACHE_RANGE;
+  return NF_OK;
+}
+
+int32_t nf_cache_write(float *cache, int32_t *cache_labels, int64_t capacity, int64_t sample_elems,
+                       int64_t first, int32_t B, const float *y, const int32_t *labels, void *stream) {
+  const int32_t rc = check_cache(cache, cache_labels, capacity, sample_elems, first, B, y, labels);
+  if (rc) return rc;
+  NF_HIP(launch_cache_copy(y, cache, labels, cache_labels, sample_elems, 0, first, nullptr, capacity, B,
+                           static_cast<hipStream_t>(stream)));
+  return NF_OK;
+}
+
+int32_t nf_cache_read(const float *cache, const int32_t *cache_labels, int64_t capacity, int64_t sample_elems,
+                      int64_t first, const int64_t *idx, int32_t B, float *x_out, int32_t *labels_out,
+                      void *stream) {
+  const int32_t rc = check_cache(cache, cache_labels, capacity, sample_elems, idx ? 0 : first, idx ? 1 : B, x_out,
+                                 labels_out);
+  if (rc) return rc;
+  if (B <= 0 || B > 65535) return NF_ERR_BAD_DESC;
+  NF_HIP(launch_cache_copy(cache, x_out, cache_labels, labels_out, sample_elems, first, 0,
+                           reinterpret_cast<const long long *>(idx), capacity, B,
+                           static_cast<hipStream_t>(stream)));
+  return NF_OK;
+}
+
+int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd_desc *s, int32_t B,
+                      const float *x, const float *x_skip, const int32_t *labels, const nf_layer_params *p,
+                      const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga,
+                      const nf_layer_params *vp, const nf_aux_params *va, float *y_out, float *loss_out,
+                      void *ws, size_t ws_bytes, void *stream) {
+  LayerDims ld;
+  AuxDims ad;
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_aux(a, &ad))) return rc;
+  if ((rc = check_pair(d, ld, a))) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if (!s || !labels || !y_out || !loss_out) return NF_ERR_NULL;
+  if ((rc = check_layer_ptrs(d, x, x_skip, p))) return rc;
+  if ((rc = check_aux_ptrs(ap))) return rc;
+  if ((rc = check_layer_ptrs(d, x, x_skip, gp))) return rc;
+  if ((rc = check_aux_ptrs(ga))) return rc;
+  if (s->momentum != 0.f) {
+    if (!vp || !va) return NF_ERR_NULL;
+    if ((rc = check_layer_ptrs(d, x, x_skip, vp))) return rc;
+    if ((rc = check_aux_ptrs(va))) return rc;
+  }
+  if (!aligned16(y_out)) return NF_ERR_BAD_DESC;
+  const WsLayout w = ws_layout(d, ld, a, ad, B);
+  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // Algorithm 2: forward with the current weights (this y_out is what the next layer reads),
+  // head + loss, local gradients, update.
+  if ((rc = run_layer_fwd(d, ld, B, x, x_skip, p, y_out, ws, w, st))) return rc;
+  if ((rc = run_aux_fwd(a, ad, B, y_out, labels, ap, loss_out, ws, w, st))) return rc;
+  if ((rc = run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, ws, w, st))) return rc;
+  SgdTensors t;
+  std::memset(&t, 0, sizeof(t));
+  t.n = collect_sgd(d, a, ad, p, ap, gp, ga, s->momentum != 0.f ? vp : nullptr, s->momentum != 0.f ? va : nullptr, &t);
+  t.lr = s->lr, t.mu = s->momentum;
+  NF_HIP(launch_sgd(t, st));
+  return NF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Internal declarations shared by the translation units of libnf (host side + kernel
+// argument structs).  Nothing here is part of the public ABI (include/nf.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/nf.h"
+
+namespace nf {
+
+// q = n / d for 0 <= n < 2^31 by multiply-high; computed once on the host.
+struct FastDiv {
+  uint32_t magic, shift, d;
+  FastDiv() : magic(0), shift(0), d(1) {}
+  explicit FastDiv(uint32_t div) : d(div) {
+    uint32_t l = 0;
+    while ((1u << l) < div) ++l;  // l = ceil(log2 d)
+    magic = (uint32_t)(((1ull << (31 + l)) / div) + 1ull);
+    shift = 31 + l;
+  }
+  __host__ __device__ inline uint32_t div(uint32_t n) const {
+    return (uint32_t)(((uint64_t)n * magic) >> shift);
+  }
+};
+
+// ---- implicit-GEMM forward-type convolution: out[m][n] = sum_kg col(x)[m][kg] * w[n][kg] ----
+// m = (img, ho, wo) row-major; kg = (r, s, c) then an optional extra tap of Cs channels read
+// from xs at (ho*ss, wo*ss) with weights wp[n][c] (the 1x1 strided projection shortcut).
+struct FwdProblem {
+  const float *x, *w, *xs, *wp, *bias;
+  const float *addsrc;  // identity shortcut [M][N] added before the ReLU (or null)
+  const float *mask;    // out is zeroed where mask[m][n] <= 0 (or null)
+  float *out;           // [M][N]
+  int H, W, C, N, R, S, stride, pad, Ho, Wo;
+  int Cs, Hs, Ws, ss;
+  int relu;
+  int M, RSC, Kg;
+  FastDiv div_howo, div_wo;
+};
+hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st);
+
+// ---- implicit-GEMM weight gradient: part[z][p][q] = sum_{m in split z} d[m][p] * col(x)[m][q]
+struct WgradProblem {
+  const float *d, *x, *xs;
+  float *part;    // [splits][P][Qld]
+  float *part_b;  // [splits][P] column sums of d (bias gradient partials)
+  int H, W, C, R, S, stride, pad, Ho, Wo;
+  int Cs, Hs, Ws, ss;
+  int P, M, RSC, Q, Qld;
+  int splits, m_per_split;
+  FastDiv div_howo, div_wo;
+};
+// chooses the tile shape for (P,Q); reports how many splits of M it wants
+int wgrad_pick_splits(int P, int Q, int M);
+hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st);
+// out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length Q-Q0) = sum_z part[z][p][q];
+// ob[p] = sum_z part_b[z][p]
+hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int splits, int P, int Q, int Qld,
+                               int Q0, float *out0, float *out1, float *ob, hipStream_t st);
+
+// ---- head (Eq. 2 after the aux conv, Eq. 3) ----
+struct HeadShape {
+  int B, Hu, Wu, A, oh, ow, F, Cls, relu;
+};
+hipError_t launch_head_fwd(const HeadShape &h, const float *U, const int32_t *labels, const float *Wf,
+                           const float *bf, float *Pq, float *dz, float *loss_n, float *loss_out,
+                           hipStream_t st);
+hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, const float *Wf, float *dWf,
+                         float *dbf, float *dPq, hipStream_t st);
+hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU,
+                                hipStream_t st);
+
+// ---- elementwise / data movement ----
+hipError_t launch_flip_transpose(const float *Wa, float *WaT, int A, int R, int S, int K, hipStream_t st);
+hipError_t launch_maxpool_fwd(const float *T, float *Y, uint8_t *arg, int B, int Ho, int Wo, int K, int Hp,
+                              int Wp, int pk, int ps, int pp, hipStream_t st);
+hipError_t launch_maxpool_bwd(const float *dY, const float *Y, const uint8_t *arg, float *dZ, int B, int Ho,
+                              int Wo, int K, int Hp, int Wp, int pk, int ps, int pp, hipStream_t st);
+struct SgdTensors {
+  float *w[16];
+  const float *g[16];
+  float *v[16];
+  long long numel[16];
+  int n;
+  float lr, mu;
+};
+hipError_t launch_sgd(const SgdTensors &t, hipStream_t st);
+hipError_t launch_cache_copy(const float *src, float *dst, const int32_t *src_lab, int32_t *dst_lab,
+                             long long sample_elems, long long src_first, long long dst_first,
+                             const long long *idx, long long capacity, int B, hipStream_t st);
+
+}  // namespace nf

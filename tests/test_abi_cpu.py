@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2402_14139_amd import binding as nf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(nf.LIB_PATH):
+        from paper_2402_14139_amd import build
+        build.build()
+    return nf.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    text = open(os.path.join(ROOT, "include", "nf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(nf_[a-z_]+)\s*\(", text))
+    assert declared == set(nf.EXPORTS), declared ^ set(nf.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def _layer(**kw):
+    base = dict(C_in=8, H_in=8, W_in=8, C_out=16, R=3, S=3, stride=1, pad=1, pool_kind=0, pool_k=0, pool_stride=0,
+                pool_pad=0, skip_kind=0, skip_C=0, skip_H=0, skip_W=0, skip_stride=0)
+    base.update(kw)
+    return nf.LayerDesc(**base)
+
+
+def _aux(**kw):
+    base = dict(C_in=16, H_in=8, W_in=8, A=8, R=3, S=3, pad=1, relu=1, pool_oh=2, pool_ow=2, n_classes=10)
+    base.update(kw)
+    return nf.AuxDesc(**base)
+
+
+def test_out_dims_and_workspace(L):
+    assert nf.nf_layer_out_dims(_layer()) == (8, 8, 8, 8)
+    assert nf.nf_layer_out_dims(_layer(stride=2)) == (4, 4, 4, 4)
+    assert nf.nf_layer_out_dims(_layer(pool_kind=1, pool_k=2, pool_stride=2)) == (8, 8, 4, 4)
+    assert nf.nf_layer_out_dims(_layer(H_in=128, W_in=128, R=7, S=7, stride=2, pad=3, pool_kind=1, pool_k=3,
+                                       pool_stride=2, pool_pad=1)) == (64, 64, 32, 32)
+    fwd_only = nf.nf_workspace_bytes(_layer(), None, 4)
+    full = nf.nf_workspace_bytes(_layer(), _aux(), 4)
+    assert 0 < fwd_only <= full and full % 256 == 0
+    assert nf.nf_workspace_bytes(_layer(), _aux(), 8) > full
+
+
+@pytest.mark.parametrize("desc,status", [
+    (dict(C_in=0), nf.NF_ERR_BAD_DESC),
+    (dict(H_in=1, W_in=1, pad=0), nf.NF_ERR_BAD_DESC),          # filter larger than padded input
+    (dict(pool_kind=2, pool_k=2, pool_stride=2), nf.NF_ERR_UNSUPPORTED),
+    (dict(pool_kind=1, pool_k=2, pool_stride=2, pool_pad=2), nf.NF_ERR_BAD_DESC),
+    (dict(skip_kind=1, skip_C=16, skip_H=4, skip_W=8), nf.NF_ERR_BAD_DESC),
+    (dict(skip_kind=2, skip_C=8, skip_H=8, skip_W=8, skip_stride=2), nf.NF_ERR_BAD_DESC),  # reads past x_skip
+    (dict(skip_kind=3), nf.NF_ERR_BAD_DESC),
+    (dict(stride=9), nf.NF_ERR_UNSUPPORTED),
+])
+def test_bad_layer_descriptors(L, desc, status):
+    out = C.c_size_t()
+    assert L.nf_workspace_bytes(C.byref(_layer(**desc)), None, 4, C.byref(out)) == status
+
+
+def test_bad_aux_and_pairing(L):
+    out = C.c_size_t()
+    d = _layer()
+    assert L.nf_workspace_bytes(C.byref(d), C.byref(_aux(C_in=8)), 4, C.byref(out)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_workspace_bytes(C.byref(d), C.byref(_aux(A=0)), 4, C.byref(out)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_workspace_bytes(C.byref(d), C.byref(_aux(R=3, S=5)), 4, C.byref(out)) == nf.NF_ERR_UNSUPPORTED
+    assert L.nf_workspace_bytes(C.byref(d), C.byref(_aux()), 0, C.byref(out)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_workspace_bytes(C.byref(d), C.byref(_aux()), 4, None) == nf.NF_ERR_NULL
+    assert L.nf_workspace_bytes(None, None, 4, C.byref(out)) == nf.NF_ERR_NULL
+
+
+def test_calls_validate_before_enqueue(L):
+    """Fake (never dereferenced) device addresses: every call must fail in validation."""
+    d, a = _layer(), _aux()
+    good, odd = 0x10000, 0x10004
+    p = nf.LayerParams(good, good, None)
+    ap = nf.AuxParams(good, good, good, good)
+    ws_bytes = nf.nf_workspace_bytes(d, a, 4)
+    # NULL pointers
+    assert L.nf_layer_fwd(C.byref(d), 4, None, None, C.byref(p), good, good, ws_bytes, None) == nf.NF_ERR_NULL
+    assert L.nf_layer_fwd(C.byref(d), 4, good, None, None, good, good, ws_bytes, None) == nf.NF_ERR_NULL
+    assert L.nf_layer_fwd(C.byref(d), 4, good, None, C.byref(nf.LayerParams(good, None, None)), good, good,
+                          ws_bytes, None) == nf.NF_ERR_NULL
+    dsk = _layer(skip_kind=1, skip_C=16, skip_H=8, skip_W=8)
+    assert L.nf_layer_fwd(C.byref(dsk), 4, good, None, C.byref(p), good, good, ws_bytes, None) == nf.NF_ERR_NULL
+    # misaligned pointer
+    assert L.nf_layer_fwd(C.byref(d), 4, odd, None, C.byref(p), good, good, ws_bytes, None) == nf.NF_ERR_BAD_DESC
+    # workspace: missing, misaligned, too small
+    dp = _layer(pool_kind=1, pool_k=2, pool_stride=2)
+    need = nf.nf_workspace_bytes(dp, None, 4)
+    assert L.nf_layer_fwd(C.byref(dp), 4, good, None, C.byref(p), good, None, need, None) == nf.NF_ERR_WORKSPACE
+    assert L.nf_layer_fwd(C.byref(dp), 4, good, None, C.byref(p), good, 0x10010, need, None) == nf.NF_ERR_WORKSPACE
+    assert L.nf_layer_fwd(C.byref(dp), 4, good, None, C.byref(p), good, good, need - 1, None) == nf.NF_ERR_WORKSPACE
+    assert L.nf_aux_fwd_loss(C.byref(d), C.byref(a), 4, good, good, C.byref(ap), good, good, ws_bytes - 1,
+                             None) == nf.NF_ERR_WORKSPACE
+    assert L.nf_aux_fwd_loss(C.byref(d), C.byref(a), 4, good, None, C.byref(ap), good, good, ws_bytes,
+                             None) == nf.NF_ERR_NULL
+    assert L.nf_local_bwd_wgrad(C.byref(d), C.byref(a), 4, good, None, good, C.byref(p), C.byref(ap), C.byref(p),
+                                None, good, ws_bytes, None) == nf.NF_ERR_NULL
+    s = nf.SgdDesc(0.1, 0.9)
+    assert L.nf_local_step(C.byref(d), C.byref(a), C.byref(s), 4, good, None, good, C.byref(p), C.byref(ap),
+                           C.byref(p), C.byref(ap), None, None, good, good, good, ws_bytes,
+                           None) == nf.NF_ERR_NULL  # momentum without momentum buffers
+    # cache ranges
+    assert L.nf_cache_write(good, good, 10, 64, 8, 4, good, good, None) == nf.NF_ERR_CACHE_RANGE
+    assert L.nf_cache_write(good, good, 10, 64, -1, 4, good, good, None) == nf.NF_ERR_CACHE_RANGE
+    assert L.nf_cache_write(good, None, 10, 64, 0, 4, good, good, None) == nf.NF_ERR_NULL
+    assert L.nf_cache_read(good, good, 10, 64, 7, None, 4, good, good, None) == nf.NF_ERR_CACHE_RANGE
+    assert L.nf_cache_read(good, good, 10, 0, 0, None, 4, good, good, None) == nf.NF_ERR_BAD_DESC
+    # sgd
+    arr = (C.c_void_p * 1)(good)
+    n1 = (C.c_int64 * 1)(16)
+    assert L.nf_sgd_update(C.byref(s), 1, arr, arr, None, n1, None) == nf.NF_ERR_NULL
+    assert L.nf_sgd_update(C.byref(s), 17, arr, arr, arr, n1, None) == nf.NF_ERR_BAD_DESC
+    assert L.nf_sgd_update(C.byref(s), 1, arr, arr, arr, (C.c_int64 * 1)(0), None) == nf.NF_ERR_BAD_DESC
+
+
+def test_strerror(L):
+    assert nf.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert nf.strerror(code) and nf.strerror(code) != "unknown status"
+    assert nf.strerror(-99) == "unknown status"
