@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""Benchmark of the local training step on one MI355X.
+
+A *step* is one pass of the whole hot path over one batch per block of the workload
+(default: the ResNet-18-style configuration, 17 local layers in 4 blocks at batch
+64/128/256/512): for every block, gather its batch from the previous block's activation
+cache at the block's own batch size (nf_cache_read with a shuffled index list; block 1
+gathers raw inputs), run nf_local_step for each of its layers (forward, head, loss, local
+gradients, SGD with momentum), and store the block's emitted activations in the next cache
+(nf_cache_write).  All inputs are synthetic, seeded, and resident in HBM before timing.
+
+Prints ONE JSON line: images/s over the timed steps, plus `roofline` for the kernel that
+takes the most time (per-launch algorithmic FLOPs / HIP-event duration against the fp32
+MFMA peak) and `cpu_baseline` (the CPU oracle timed on a bounded sample of the same work).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+
+
+def layer_flops(ls, B, n_classes):
+    """Algorithmic FLOPs of one local step: fwd + wgrad for the layer (and projection),
+    fwd + wgrad + dgrad for the aux conv and the linear layer (dense formula)."""
+    f_layer = 2.0 * B * ls.Ho * ls.Wo * ls.C_out * ls.C_in * ls.R * ls.S
+    f_proj = 2.0 * B * ls.Ho * ls.Wo * ls.C_out * ls.skip_C if ls.skip_kind == 2 else 0.0
+    f_aux = 2.0 * B * ls.Hp * ls.Wp * ls.A * ls.C_out * 9
+    f_fc = 2.0 * B * 4 * ls.A * n_classes
+    return 2.0 * (f_layer + f_proj) + 3.0 * f_aux + 3.0 * f_fc
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--samples", type=int, default=0, help="synthetic data-set size (default: the config's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prof", action="store_true")
+    ap.add_argument("--lr", type=float, default=None, help="override the configuration's learning rate")
+    ap.add_argument("--trace-loss", action="store_true", help="print every layer's loss after each step (syncs)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    from paper_2402_14139_amd import binding as nf
+    from paper_2402_14139_amd import layout
+    from paper_2402_14139_amd.layer import LocalLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    nf.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = workloads.config(args.config)
+    if args.lr is not None:
+        cfg.lr = args.lr
+    N = args.samples or cfg.n_samples
+    maxB = max(b.batch for b in cfg.blocks)
+    N = max(N // maxB, 1) * maxB
+    cls = cfg.n_classes
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)  # noqa: E731
+    log(f"[bench] {cfg.name}: {len(cfg.layers)} layers, {len(cfg.blocks)} blocks, N={N}")
+
+    # ---- parameters and per-layer device state ------------------------------------------------
+    layers = []
+    for li, ls in enumerate(cfg.layers):
+        p = workloads.gen_layer_params(cfg.seed, li, ls, cls)
+        d, a = nf.LayerDesc(**ls.layer_desc_fields()), nf.AuxDesc(**ls.aux_desc_fields(cls))
+        B = cfg.blocks[ls.block].batch
+        L = LocalLayer(d, a, layout.params_to_lib(p, ls.A), B, momentum=cfg.momentum != 0, device=dev)
+        L.y = L.new_output(B)
+        layers.append(L)
+
+    # ---- synthetic data set (rows = samples, NHWC) and the caches between blocks ---------------
+    g = workloads.rng_for(cfg.seed, "bench-data")
+    C0, H0, W0 = cfg.in_shape
+    se0 = C0 * H0 * W0
+    data = torch.empty((N, se0), dtype=torch.float32, device=dev)
+    chunk = 1024
+    for i in range(0, N, chunk):
+        n = min(chunk, N - i)
+        data[i:i + n] = torch.from_numpy(g.standard_normal((n, se0)).astype(np.float32)).to(dev)
+    labels = torch.from_numpy(g.integers(0, cls, size=(N,)).astype(np.int32)).to(dev)
+    nblk = len(cfg.blocks)
+    se = [se0]
+    for b in cfg.blocks:
+        last = cfg.layers[b.layers[-1]]
+        se.append(last.C_out * last.Hp * last.Wp)
+    caches = [data] + [torch.empty((N, se[k + 1]), dtype=torch.float32, device=dev) for k in range(nblk - 1)]
+    clabels = [labels] + [torch.empty((N,), dtype=torch.int32, device=dev) for _ in range(nblk - 1)]
+    # Timed steps write each block's output into a second set of caches: in the method a cache is
+    # written once, after its block has been trained, and only read afterwards; writing the
+    # half-trained outputs into the caches the next block is reading from would feed the blocks'
+    # evolving weights back into their own inputs.
+    wcaches = [None] + [torch.empty_like(c) for c in caches[1:]]
+    wlabels = [None] + [torch.empty_like(c) for c in clabels[1:]]
+    xin = []
+    lin = []
+    for k, b in enumerate(cfg.blocks):
+        f = cfg.layers[b.layers[0]]
+        xin.append(torch.empty((b.batch, f.H_in, f.W_in, f.C_in), dtype=torch.float32, device=dev))
+        lin.append(torch.empty((b.batch,), dtype=torch.int32, device=dev))
+    perms = [torch.from_numpy(workloads.rng_for(cfg.seed, "perm", k).permutation(N).astype(np.int64)).to(dev)
+             for k in range(nblk)]
+
+    def skip_of(li, x_block):
+        ls = cfg.layers[li]
+        if not ls.skip_kind:
+            return None
+        src = ls.skip_src  # the layer whose INPUT is the shortcut tensor
+        first = cfg.blocks[ls.block].layers[0]
+        return x_block if src == first else layers[src - 1].y
+
+    def block_forward(k, x):
+        b = cfg.blocks[k]
+        cur = x
+        for li in b.layers:
+            layers[li].forward(cur, skip_of(li, x), layers[li].y)
+            cur = layers[li].y
+        return cur
+
+    def block_step(k, x, lab):
+        b = cfg.blocks[k]
+        cur = x
+        for li in b.layers:
+            layers[li].step(cur, skip_of(li, x), lab, cfg.lr, cfg.momentum, layers[li].y)
+            cur = layers[li].y
+        return cur
+
+    # fill the caches once with the initial weights so deeper blocks see real activations
+    t0 = time.time()
+    for k in range(nblk - 1):
+        B = cfg.blocks[k].batch
+        for first in range(0, N, B):
+            nf.nf_cache_read(caches[k], clabels[k], N, se[k], first, None, B, xin[k], lin[k])
+            y = block_forward(k, xin[k])
+            nf.nf_cache_write(caches[k + 1], clabels[k + 1], N, se[k + 1], first, B, y, lin[k])
+    torch.cuda.synchronize()
+    log(f"[bench] caches filled in {time.time() - t0:.1f}s "
+        f"({sum(c.numel() for c in caches[1:]) * 4 / 2**30:.2f} GiB)")
+
+    def one_step(s):
+        for k in range(nblk):
+            B = cfg.blocks[k].batch
+            j = s % (N // B)
+            nf.nf_cache_read(caches[k], clabels[k], N, se[k], 0, perms[k][j * B:(j + 1) * B], B, xin[k], lin[k])
+            y = block_step(k, xin[k], lin[k])
+            if k + 1 < nblk:
+                nf.nf_cache_write(wcaches[k + 1], wlabels[k + 1], N, se[k + 1], j * B, B, y, lin[k])
+        if args.trace_loss:
+            torch.cuda.synchronize()
+            log(f"[loss] step {s}: " + " ".join(f"{float(L.loss.item()):.3f}" for L in layers)
+                + " | ymax " + " ".join(f"{float(L.y.max()):.1f}" for L in layers))
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, args.warmup + args.steps):
+        one_step(s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    images_per_step = sum(b.batch for b in cfg.blocks)
+    flops_per_step = sum(layer_flops(ls, cfg.blocks[ls.block].batch, cls) for ls in cfg.layers)
+    losses = [float(L.loss.item()) for L in layers]
+    assert all(np.isfinite(losses)), losses
+    log(f"[bench] {ms_per_step:.3f} ms/step, {flops_per_step / 1e9:.1f} GFLOP/step, "
+        f"{flops_per_step / dt * args.steps / 1e12:.2f} TFLOP/s")
+
+    # ---- per-kernel timing with HIP events: the same steps again ------------------------------
+    roofline, kernels = None, []
+    if not args.no_prof:
+        psteps = min(args.steps, 5)
+        nf.nf_prof_begin()
+        for s in range(psteps):
+            one_step(args.warmup + args.steps + s)
+        recs = nf.nf_prof_end()
+        tot = sum(r["ms"] for r in recs)
+        for r in recs:
+            kernels.append({"kernel": r["kernel"], "launches_per_step": r["launches"] / psteps,
+                            "ms_per_step": round(r["ms"] / psteps, 4), "share": round(r["ms"] / tot, 4),
+                            "avg_us": round(1e3 * r["ms"] / r["launches"], 2),
+                            "tflops": round(r["flops"] / (r["ms"] * 1e-3) / 1e12, 2) if r["flops"] else 0.0,
+                            "gbs": round(r["bytes"] / (r["ms"] * 1e-3) / 1e9, 1)})
+        dom = recs[0]
+        if dom["kernel"].startswith("igemm"):
+            ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+            roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": round(ach, 2),
+                        "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_F32_PEAK_TFLOPS, 4),
+                        "traffic": None, "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
+                        "measured_over": f"{psteps} further steps with one HIP-event pair per kernel launch"}
+        else:
+            ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+            roofline = {"kernel": dom["kernel"], "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                        "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
+                        "measured_over": f"{psteps} further steps with one HIP-event pair per kernel launch"}
+        for kr in kernels:
+            log(f"[kernel] {kr['kernel']:<26} {kr['launches_per_step']:6.1f}/step {kr['ms_per_step']:9.4f} ms "
+                f"{100 * kr['share']:5.1f}%  avg {kr['avg_us']:9.2f} us  {kr['tflops']:7.2f} TFLOP/s {kr['gbs']:8.1f} GB/s")
+
+    # ---- per-layer step times (one event pair per local step) ---------------------------------
+    per_layer = []
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in cfg.layers]
+    acc = [0.0] * len(cfg.layers)
+    reps = 3
+    for r in range(reps):
+        for k in range(nblk):
+            b = cfg.blocks[k]
+            cur = xin[k]
+            for li in b.layers:
+                evs[li][0].record()
+                layers[li].step(cur, skip_of(li, xin[k]), lin[k], cfg.lr, cfg.momentum, layers[li].y)
+                evs[li][1].record()
+                cur = layers[li].y
+        torch.cuda.synchronize()
+        for li in range(len(cfg.layers)):
+            acc[li] += evs[li][0].elapsed_time(evs[li][1])
+    for li, ls in enumerate(cfg.layers):
+        B = cfg.blocks[ls.block].batch
+        ms = acc[li] / reps
+        fl = layer_flops(ls, B, cls)
+        per_layer.append({"layer": ls.name, "block": ls.block, "B": B, "ms": round(ms, 4),
+                          "images_per_s": round(B / (ms * 1e-3), 1), "tflops": round(fl / (ms * 1e-3) / 1e12, 2)})
+        log(f"[layer] {li:2d} {ls.name:<8} blk{ls.block} B={B:<4d} {ms:8.3f} ms {B / (ms * 1e-3):10.0f} img/s "
+            f"{fl / (ms * 1e-3) / 1e12:7.2f} TFLOP/s")
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as O
+        blk = cfg.blocks[0]
+        B = blk.batch
+        xb, yb = workloads.gen_batch(cfg.seed, 0, B, cfg.in_shape, cls)
+        specs = [cfg.layers[li] for li in blk.layers]
+        params = [workloads.gen_layer_params(cfg.seed, li, cfg.layers[li], cls) for li in blk.layers]
+        moms = [{k: (None if v is None else np.zeros_like(v)) for k, v in p.items()} for p in params]
+        t0 = time.perf_counter()
+        cur, outs = xb, {}
+        for i, (li, ls) in enumerate(zip(blk.layers, specs)):
+            xs = None
+            if ls.skip_kind:
+                xs = xb if ls.skip_src == blk.layers[0] else outs[ls.skip_src - 1]
+            od, oa = O.layer_desc(**ls.layer_desc_fields()), O.aux_desc(**ls.aux_desc_fields(cls))
+            Y, _, _ = O.local_step(od, oa, cur, xs, yb, params[i], moms[i], cfg.lr, cfg.momentum)
+            outs[li] = Y
+            cur = Y
+        t_cpu = time.perf_counter() - t0
+        fl_sample = sum(layer_flops(ls, B, cls) for ls in specs)
+        scaled_step_s = t_cpu * flops_per_step / fl_sample
+        cpu = {"value": round(images_per_step / scaled_step_s, 3), "unit": "images/s", "cores": O.num_threads(),
+               "kind": "oracle",
+               "sample": f"block 1 of {cfg.name} (its {len(specs)} layers, one local step each at B={B}: "
+                         f"{fl_sample / 1e9:.1f} of the step's {flops_per_step / 1e9:.1f} GFLOP) took {t_cpu:.2f} s; "
+                         f"scaled by FLOPs to the full step",
+               "gflops": round(fl_sample / t_cpu / 1e9, 2)}
+        log(f"[cpu] oracle {t_cpu:.2f}s on {O.num_threads()} threads, {fl_sample / t_cpu / 1e9:.2f} GFLOP/s")
+
+    tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "local_step_images_per_sec", "value": round(images_per_step / (ms_per_step * 1e-3), 1),
+        "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: one local step of each of {len(cfg.layers)} layers at block batches "
+                               f"{'/'.join(str(b.batch) for b in cfg.blocks)}, {cls} classes, SGD lr {cfg.lr} "
+                               f"momentum {cfg.momentum}, cache read (shuffled gather) before and cache write after "
+                               f"every block", "images_per_step": images_per_step, "samples": N,
+                   "gflop_per_step": round(flops_per_step / 1e9, 1)},
+        "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "layers": per_layer,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -146,6 +146,21 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
                       const nf_aux_params *ga, const nf_layer_params *vp, const nf_aux_params *va,
                       float *y_out, float *loss_out, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- measurement aid (not a step of the method) ---------------------------------------------
+ * Between nf_prof_begin and nf_prof_end every kernel the library enqueues is bracketed by a
+ * HIP-event pair on the caller's stream.  nf_prof_end waits for those events (the only call
+ * that blocks the host), and returns one record per kernel: launches, summed duration (ms),
+ * summed algorithmic FLOPs and bytes.  Records are sorted by duration, at most `cap` are
+ * written, *n receives the number of distinct kernels.  Process-wide, not thread-safe, creates
+ * HIP events: keep it out of production loops. */
+typedef struct {
+  char kernel[48];
+  int64_t launches;
+  double ms, flops, bytes;
+} nf_prof_record;
+int32_t nf_prof_begin(void);
+int32_t nf_prof_end(nf_prof_record *out, int32_t cap, int32_t *n);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,8 @@ NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE
     -1, -2, -3, -4, -5, -6)
 
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
-           "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step")
+           "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
+           "nf_prof_begin", "nf_prof_end")
 
 
 class NfError(RuntimeError):
@@ -45,6 +46,11 @@ class SgdDesc(C.Structure):
 
 class LayerParams(C.Structure):
     _fields_ = [("W", C.c_void_p), ("b", C.c_void_p), ("Wp", C.c_void_p)]
+
+
+class ProfRecord(C.Structure):
+    _fields_ = [("kernel", C.c_char * 48), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
 
 
 class AuxParams(C.Structure):
@@ -87,6 +93,7 @@ def lib():
                                     C.POINTER(LayerParams), C.POINTER(AuxParams), C.POINTER(LayerParams),
                                     C.POINTER(AuxParams), C.POINTER(LayerParams), C.POINTER(AuxParams),
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_prof_end.argtypes = [C.POINTER(ProfRecord), C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -190,3 +197,16 @@ def nf_local_step(d, a, lr, momentum, B, x, x_skip, labels, p, ap, gp, ga, vp, v
                                C.byref(p), C.byref(ap), C.byref(gp), C.byref(ga),
                                C.byref(vp) if vp is not None else None, C.byref(va) if va is not None else None,
                                _ptr(y_out), _ptr(loss_out), wp, wn, _stream(stream)), "nf_local_step")
+
+
+def nf_prof_begin():
+    _check(lib().nf_prof_begin(), "nf_prof_begin")
+
+
+def nf_prof_end(cap: int = 64):
+    """list of dicts {kernel, launches, ms, flops, bytes}, sorted by total duration."""
+    recs = (ProfRecord * cap)()
+    n = C.c_int32()
+    _check(lib().nf_prof_end(recs, cap, C.byref(n)), "nf_prof_end")
+    return [dict(kernel=recs[i].kernel.decode(), launches=int(recs[i].launches), ms=float(recs[i].ms),
+                 flops=float(recs[i].flops), bytes=float(recs[i].bytes)) for i in range(min(n.value, cap))]

@@ -179,16 +179,17 @@ __global__ __launch_bounds__(HT) void pool_relu_bwd_kernel(HeadShape s, const fl
 }  // namespace
 
 hipError_t launch_head_fwd(const HeadShape &h, const float *U, const int32_t *labels, const float *Wf,
-                           const float *bf, float *Pq, float *dz, float *loss_n, float *loss_out,
-                           hipStream_t st) {
+                           const float *bf, float *Pq, float *dz, float *loss_n, hipStream_t st) {
   int G = 1;
   const int rows = (h.Hu + h.oh - 1) / h.oh;
   while (G * 2 * h.F <= 2 * HT && G * 2 <= rows) G *= 2;
   const size_t lds = (size_t)(h.F + h.Cls + G * h.F + 8) * sizeof(float);
   hipLaunchKernelGGL(head_fwd_kernel, dim3(h.B), dim3(HT), lds, st, h, U, labels, Wf, bf, Pq, dz, loss_n, G);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(HT), 0, st, loss_n, h.B, loss_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStream_t st) {
+  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(HT), 0, st, loss_n, B, loss_out);
   return hipGetLastError();
 }
 

@@ -244,10 +244,17 @@ hipError_t launch_cfg(const FwdProblem &p, bool vec, hipStream_t st) {
 
 }  // namespace
 
-hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st) {
+hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **kernel) {
   const bool vec = (p.C % 4 == 0) && (p.Cs % 4 == 0);
-  if (p.N > 64) return launch_cfg<128, 128, 2, 2>(p, vec, st);
-  if (p.N > 32) return launch_cfg<128, 64, 2, 2>(p, vec, st);
+  if (p.N > 64) {
+    *kernel = vec ? "igemm_fwd_128x128_v4" : "igemm_fwd_128x128_v1";
+    return launch_cfg<128, 128, 2, 2>(p, vec, st);
+  }
+  if (p.N > 32) {
+    *kernel = vec ? "igemm_fwd_128x64_v4" : "igemm_fwd_128x64_v1";
+    return launch_cfg<128, 64, 2, 2>(p, vec, st);
+  }
+  *kernel = vec ? "igemm_fwd_128x32_v4" : "igemm_fwd_128x32_v1";
   return launch_cfg<128, 32, 4, 1>(p, vec, st);
 }
 

@@ -276,10 +276,17 @@ int wgrad_pick_splits(int P, int Q, int M) {
   return (int)want;
 }
 
-hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st) {
+hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char **kernel) {
   const bool vec = (p.C % 4 == 0) && (p.Cs % 4 == 0) && (p.P % 4 == 0);
-  if (p.P > 64) return launch_cfg<128, 128, 2, 2>(p, vec, st);
-  if (p.P > 32) return launch_cfg<64, 128, 2, 2>(p, vec, st);
+  if (p.P > 64) {
+    *kernel = vec ? "igemm_wgrad_128x128_v4" : "igemm_wgrad_128x128_v1";
+    return launch_cfg<128, 128, 2, 2>(p, vec, st);
+  }
+  if (p.P > 32) {
+    *kernel = vec ? "igemm_wgrad_64x128_v4" : "igemm_wgrad_64x128_v1";
+    return launch_cfg<64, 128, 2, 2>(p, vec, st);
+  }
+  *kernel = vec ? "igemm_wgrad_32x256_v4" : "igemm_wgrad_32x256_v1";
   return launch_cfg<32, 256, 1, 4>(p, vec, st);
 }
 

@@ -1,8 +1,10 @@
 // C-ABI entry points of libnf (include/nf.h): argument validation, workspace layout and the
 // order in which the kernels of one local training step are enqueued (body of Algorithm 2,
 // NeuroFlux, arXiv 2402.14139).  No device work is enqueued before validation has passed.
+#include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <vector>
 
 #include "nf_internal.h"
 
@@ -140,7 +142,72 @@ inline float *wsf(void *ws, size_t off) { return reinterpret_cast<float *>(stati
     if ((expr) != hipSuccess) return NF_ERR_DEVICE; \
   } while (0)
 
+// ---- optional kernel timing (nf_prof_begin / nf_prof_end): one HIP-event pair per launch ----
+struct ProfEvent {
+  const char *name;
+  hipEvent_t a, b;
+  double flops, bytes;
+};
+struct ProfState {
+  bool on = false;
+  std::vector<ProfEvent> ev;
+};
+ProfState g_prof;
+
+struct ProfScope {
+  hipStream_t st;
+  hipEvent_t a = nullptr, b = nullptr;
+  bool on;
+  explicit ProfScope(hipStream_t s) : st(s), on(g_prof.on) {
+    if (on) {
+      on = hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess && hipEventRecord(a, st) == hipSuccess;
+    }
+  }
+  void done(const char *name, double flops, double bytes) {
+    if (on && hipEventRecord(b, st) == hipSuccess) g_prof.ev.push_back({name, a, b, flops, bytes});
+  }
+};
+
 // ---- enqueue helpers (arguments already validated) ----
+
+#define NF_RUN(st, name, flops, bytes, call) \
+  do {                                       \
+    ProfScope sc_(st);                       \
+    NF_HIP(call);                            \
+    sc_.done(name, flops, bytes);            \
+  } while (0)
+
+// algorithmic work of the two contractions (dense formula: padding taps counted, tile padding not)
+int32_t enqueue_fwd(const FwdProblem &f, hipStream_t st) {
+  const double B = (double)f.M / ((double)f.Ho * f.Wo);
+  const double flops = 2.0 * f.M * f.N * f.Kg;
+  double elems = B * f.H * f.W * f.C + (double)f.N * f.Kg + (double)f.M * f.N;
+  if (f.Cs) elems += B * f.Hs * f.Ws * f.Cs;
+  if (f.addsrc) elems += (double)f.M * f.N;
+  if (f.mask) elems += (double)f.M * f.N;
+  ProfScope sc(st);
+  const char *kn = "igemm_fwd";
+  NF_HIP(launch_igemm_fwd(f, st, &kn));
+  sc.done(kn, flops, 4.0 * elems);
+  return NF_OK;
+}
+
+int32_t enqueue_wgrad(const WgradProblem &g, float *out0, float *out1, float *ob, hipStream_t st) {
+  const double B = (double)g.M / ((double)g.Ho * g.Wo);
+  const double flops = 2.0 * g.M * g.P * g.Q;
+  double elems = (double)g.M * g.P + B * g.H * g.W * g.C + (double)g.P * g.Q;
+  if (g.Cs) elems += B * g.Hs * g.Ws * g.Cs;
+  {
+    ProfScope sc(st);
+    const char *kn = "igemm_wgrad";
+    NF_HIP(launch_igemm_wgrad(g, st, &kn));
+    sc.done(kn, flops, 4.0 * elems);
+  }
+  const double red = ((double)g.splits + 1.0) * g.P * (g.Q + 1.0);
+  NF_RUN(st, "wgrad_reduce", 0.0, 4.0 * red,
+         launch_wgrad_reduce(g.part, g.part_b, g.splits, g.P, g.Q, g.Qld, g.RSC, out0, out1, ob, st));
+  return NF_OK;
+}
 
 int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const float *x, const float *xs,
                       const nf_layer_params *p, float *y, void *ws, const WsLayout &w, hipStream_t st) {
@@ -156,10 +223,14 @@ int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const 
   f.M = B * ld.Ho * ld.Wo, f.RSC = d->R * d->S * d->C_in, f.Kg = f.RSC + f.Cs;
   f.div_howo = FastDiv(ld.Ho * ld.Wo), f.div_wo = FastDiv(ld.Wo);
   f.out = pooled ? wsf(ws, w.T_dZ) : y;
-  NF_HIP(launch_igemm_fwd(f, st));
-  if (pooled)
-    NF_HIP(launch_maxpool_fwd(wsf(ws, w.T_dZ), y, reinterpret_cast<uint8_t *>(wsf(ws, w.arg)), B, ld.Ho, ld.Wo,
+  int32_t rc = enqueue_fwd(f, st);
+  if (rc) return rc;
+  if (pooled) {
+    const double pre = (double)B * ld.Ho * ld.Wo * d->C_out, post = (double)B * ld.Hp * ld.Wp * d->C_out;
+    NF_RUN(st, "maxpool_fwd", 0.0, 4.0 * pre + 5.0 * post,
+           launch_maxpool_fwd(wsf(ws, w.T_dZ), y, reinterpret_cast<uint8_t *>(wsf(ws, w.arg)), B, ld.Ho, ld.Wo,
                               d->C_out, ld.Hp, ld.Wp, d->pool_k, d->pool_stride, d->pool_pad, st));
+  }
   return NF_OK;
 }
 
@@ -181,9 +252,13 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   f.M = B * ad.Hu * ad.Wu, f.RSC = a->R * a->S * a->C_in, f.Kg = f.RSC;
   f.div_howo = FastDiv(ad.Hu * ad.Wu), f.div_wo = FastDiv(ad.Wu);
   f.out = wsf(ws, w.U);
-  NF_HIP(launch_igemm_fwd(f, st));
-  NF_HIP(launch_head_fwd(head_shape(a, ad, B), wsf(ws, w.U), labels, ap->Wf, ap->bf, wsf(ws, w.Pq), wsf(ws, w.dz),
-                         wsf(ws, w.loss_n), loss_out, st));
+  int32_t rc = enqueue_fwd(f, st);
+  if (rc) return rc;
+  const HeadShape hs = head_shape(a, ad, B);
+  const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
+  NF_RUN(st, "head_fwd", 2.0 * B * fc, 4.0 * (u + fc + (double)B * (ad.F + a->n_classes)),
+         launch_head_fwd(hs, wsf(ws, w.U), labels, ap->Wf, ap->bf, wsf(ws, w.Pq), wsf(ws, w.dz), wsf(ws, w.loss_n), st));
+  NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
   return NF_OK;
 }
 
@@ -196,8 +271,11 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
   const HeadShape hs = head_shape(a, ad, B);
   float *dU = wsf(ws, w.dU), *dZ = wsf(ws, w.T_dZ);
   // gamma_n, then back through F_n and the aux ReLU
-  NF_HIP(launch_fc_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ap->Wf, ga->Wf, ga->bf, wsf(ws, w.dPq), st));
-  NF_HIP(launch_pool_relu_bwd(hs, wsf(ws, w.U), wsf(ws, w.dPq), dU, st));
+  const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
+  NF_RUN(st, "fc_bwd", 4.0 * B * fc, 4.0 * (2.0 * fc + (double)B * (2.0 * ad.F + a->n_classes)),
+         launch_fc_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ap->Wf, ga->Wf, ga->bf, wsf(ws, w.dPq), st));
+  NF_RUN(st, "pool_relu_bwd", 0.0, 4.0 * (2.0 * u + (double)B * ad.F),
+         launch_pool_relu_bwd(hs, wsf(ws, w.U), wsf(ws, w.dPq), dU, st));
   // beta_n: weight + bias gradient
   {
     WgradProblem g;
@@ -209,12 +287,14 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     g.splits = w.splits_aux;
     g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;
     g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);
-    NF_HIP(launch_igemm_wgrad(g, st));
-    NF_HIP(launch_wgrad_reduce(g.part, g.part_b, g.splits, g.P, g.Q, g.Qld, g.Q, ga->Wa, nullptr, ga->ba, st));
+    const int32_t rc = enqueue_wgrad(g, ga->Wa, nullptr, ga->ba, st);
+    if (rc) return rc;
   }
   // beta_n: data gradient w.r.t. the emitted activation, layer ReLU mask fused when un-pooled
   {
-    NF_HIP(launch_flip_transpose(ap->Wa, wsf(ws, w.WaT), a->A, a->R, a->S, a->C_in, st));
+    const double wa = (double)a->A * a->R * a->S * a->C_in;
+    NF_RUN(st, "flip_transpose", 0.0, 8.0 * wa,
+           launch_flip_transpose(ap->Wa, wsf(ws, w.WaT), a->A, a->R, a->S, a->C_in, st));
     FwdProblem f;
     std::memset((void *)&f, 0, sizeof(f));
     f.x = dU, f.w = wsf(ws, w.WaT);
@@ -224,10 +304,14 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     f.div_howo = FastDiv(a->H_in * a->W_in), f.div_wo = FastDiv(a->W_in);
     f.mask = pooled ? nullptr : y;
     f.out = pooled ? wsf(ws, w.dY) : dZ;
-    NF_HIP(launch_igemm_fwd(f, st));
-    if (pooled)
-      NF_HIP(launch_maxpool_bwd(wsf(ws, w.dY), y, reinterpret_cast<const uint8_t *>(wsf(ws, w.arg)), dZ, B, ld.Ho,
+    const int32_t rc = enqueue_fwd(f, st);
+    if (rc) return rc;
+    if (pooled) {
+      const double pre = (double)B * ld.Ho * ld.Wo * d->C_out, post = (double)B * ld.Hp * ld.Wp * d->C_out;
+      NF_RUN(st, "maxpool_bwd", 0.0, 4.0 * pre + 9.0 * post,
+             launch_maxpool_bwd(wsf(ws, w.dY), y, reinterpret_cast<const uint8_t *>(wsf(ws, w.arg)), dZ, B, ld.Ho,
                                 ld.Wo, d->C_out, ld.Hp, ld.Wp, d->pool_k, d->pool_stride, d->pool_pad, st));
+    }
   }
   // theta_n: weight, bias and projection gradients; nothing flows to x or x_skip
   {
@@ -241,9 +325,25 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     g.splits = w.splits_layer;
     g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;
     g.div_howo = FastDiv(ld.Ho * ld.Wo), g.div_wo = FastDiv(ld.Wo);
-    NF_HIP(launch_igemm_wgrad(g, st));
-    NF_HIP(launch_wgrad_reduce(g.part, g.part_b, g.splits, g.P, g.Q, g.Qld, g.RSC, gp->W, gp->Wp, gp->b, st));
+    const int32_t rc = enqueue_wgrad(g, gp->W, gp->Wp, gp->b, st);
+    if (rc) return rc;
   }
+  return NF_OK;
+}
+
+int32_t enqueue_sgd(const SgdTensors &t, hipStream_t st) {
+  double n = 0;
+  for (int i = 0; i < t.n; ++i) n += (double)t.numel[i];
+  const bool mom = t.mu != 0.f && t.v[0] != nullptr;
+  NF_RUN(st, "sgd", (mom ? 4.0 : 2.0) * n, (mom ? 20.0 : 12.0) * n, launch_sgd(t, st));
+  return NF_OK;
+}
+
+int32_t enqueue_cache_copy(const float *src, float *dst, const int32_t *sl, int32_t *dl, long long se,
+                           long long sfirst, long long dfirst, const long long *idx, long long cap, int B,
+                           hipStream_t st) {
+  NF_RUN(st, "cache_copy", 0.0, 8.0 * (double)se * B + (sl ? 8.0 * B : 0.0) + (idx ? 8.0 * B : 0.0),
+         launch_cache_copy(src, dst, sl, dl, se, sfirst, dfirst, idx, cap, B, st));
   return NF_OK;
 }
 
@@ -404,8 +504,7 @@ int32_t nf_sgd_update(const nf_sgd_desc *s, int32_t n_tensors, float *const *w, 
     t.w[i] = w[i], t.g[i] = g[i], t.v[i] = use_v ? v[i] : nullptr, t.numel[i] = numel[i];
   }
   t.n = n_tensors, t.lr = s->lr, t.mu = s->momentum;
-  NF_HIP(launch_sgd(t, static_cast<hipStream_t>(stream)));
-  return NF_OK;
+  return enqueue_sgd(t, static_cast<hipStream_t>(stream));
 }
 
 static int32_t check_cache(const void *cache, const void *clab, int64_t capacity, int64_t se, int64_t first,
@@ -422,9 +521,8 @@ int32_t nf_cache_write(float *cache, int32_t *cache_labels, int64_t capacity, in
                        int64_t first, int32_t B, const float *y, const int32_t *labels, void *stream) {
   const int32_t rc = check_cache(cache, cache_labels, capacity, sample_elems, first, B, y, labels);
   if (rc) return rc;
-  NF_HIP(launch_cache_copy(y, cache, labels, cache_labels, sample_elems, 0, first, nullptr, capacity, B,
-                           static_cast<hipStream_t>(stream)));
-  return NF_OK;
+  return enqueue_cache_copy(y, cache, labels, cache_labels, sample_elems, 0, first, nullptr, capacity, B,
+                            static_cast<hipStream_t>(stream));
 }
 
 int32_t nf_cache_read(const float *cache, const int32_t *cache_labels, int64_t capacity, int64_t sample_elems,
@@ -434,10 +532,8 @@ int32_t nf_cache_read(const float *cache, const int32_t *cache_labels, int64_t c
                                  labels_out);
   if (rc) return rc;
   if (B <= 0 || B > 65535) return NF_ERR_BAD_DESC;
-  NF_HIP(launch_cache_copy(cache, x_out, cache_labels, labels_out, sample_elems, first, 0,
-                           reinterpret_cast<const long long *>(idx), capacity, B,
-                           static_cast<hipStream_t>(stream)));
-  return NF_OK;
+  return enqueue_cache_copy(cache, x_out, cache_labels, labels_out, sample_elems, first, 0,
+                            reinterpret_cast<const long long *>(idx), capacity, B, static_cast<hipStream_t>(stream));
 }
 
 int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd_desc *s, int32_t B,
@@ -475,8 +571,44 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
   std::memset(&t, 0, sizeof(t));
   t.n = collect_sgd(d, a, ad, p, ap, gp, ga, s->momentum != 0.f ? vp : nullptr, s->momentum != 0.f ? va : nullptr, &t);
   t.lr = s->lr, t.mu = s->momentum;
-  NF_HIP(launch_sgd(t, st));
+  return enqueue_sgd(t, st);
+}
+
+int32_t nf_prof_begin(void) {
+  for (auto &e : g_prof.ev) {
+    (void)hipEventDestroy(e.a);
+    (void)hipEventDestroy(e.b);
+  }
+  g_prof.ev.clear();
+  g_prof.on = true;
   return NF_OK;
+}
+
+int32_t nf_prof_end(nf_prof_record *out, int32_t cap, int32_t *n) {
+  g_prof.on = false;
+  if (!n || (cap > 0 && !out)) return NF_ERR_NULL;
+  std::vector<nf_prof_record> agg;
+  int32_t rc = NF_OK;
+  for (auto &e : g_prof.ev) {
+    float ms = 0.f;
+    if (hipEventSynchronize(e.b) != hipSuccess || hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) rc = NF_ERR_DEVICE;
+    (void)hipEventDestroy(e.a);
+    (void)hipEventDestroy(e.b);
+    auto it = std::find_if(agg.begin(), agg.end(), [&](const nf_prof_record &r) { return !std::strcmp(r.kernel, e.name); });
+    if (it == agg.end()) {
+      nf_prof_record r;
+      std::memset(&r, 0, sizeof(r));
+      std::strncpy(r.kernel, e.name, sizeof(r.kernel) - 1);
+      agg.push_back(r);
+      it = agg.end() - 1;
+    }
+    it->launches += 1, it->ms += ms, it->flops += e.flops, it->bytes += e.bytes;
+  }
+  g_prof.ev.clear();
+  std::sort(agg.begin(), agg.end(), [](const nf_prof_record &a, const nf_prof_record &b) { return a.ms > b.ms; });
+  *n = (int32_t)agg.size();
+  for (int32_t i = 0; i < *n && i < cap; ++i) out[i] = agg[i];
+  return rc;
 }
 
 }  // extern "C"

@@ -37,7 +37,8 @@ struct FwdProblem {
   int M, RSC, Kg;
   FastDiv div_howo, div_wo;
 };
-hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st);
+// `*kernel` receives a static string naming the tile configuration that was launched
+hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **kernel);
 
 // ---- implicit-GEMM weight gradient: part[z][p][q] = sum_{m in split z} d[m][p] * col(x)[m][q]
 struct WgradProblem {
@@ -52,7 +53,7 @@ struct WgradProblem {
 };
 // chooses the tile shape for (P,Q); reports how many splits of M it wants
 int wgrad_pick_splits(int P, int Q, int M);
-hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st);
+hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char **kernel);
 // out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length Q-Q0) = sum_z part[z][p][q];
 // ob[p] = sum_z part_b[z][p]
 hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int splits, int P, int Q, int Qld,
@@ -63,8 +64,8 @@ struct HeadShape {
   int B, Hu, Wu, A, oh, ow, F, Cls, relu;
 };
 hipError_t launch_head_fwd(const HeadShape &h, const float *U, const int32_t *labels, const float *Wf,
-                           const float *bf, float *Pq, float *dz, float *loss_n, float *loss_out,
-                           hipStream_t st);
+                           const float *bf, float *Pq, float *dz, float *loss_n, hipStream_t st);
+hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStream_t st);
 hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, const float *Wf, float *dWf,
                          float *dbf, float *dPq, hipStream_t st);
 hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU,
