@@ -1,0 +1,274 @@
+// Fast path of the implicit-GEMM convolution (see igemm_fwd.hip for the GEMM view and the
+// steps of the local training step it serves; NeuroFlux, arXiv 2402.14139, Eq. 1, Eq. 2 and
+// the data gradient of beta_n).
+//
+// Requirements (checked by the launcher): channel counts multiples of 4, at most 32 filter
+// taps, every operand smaller than 2 GiB.  What differs from the general kernel:
+//   - all global reads are raw buffer loads; out-of-image taps, rows past M or N and the
+//     padding of the reduction axis are expressed as an out-of-range offset, for which the
+//     hardware returns zeros: the gather has no branches and no selects on data;
+//   - per output row the validity of every filter tap is a bit mask computed once, and the
+//     (tap, channel) decode of a thread's 16-byte chunk is two multiply-high divisions;
+//   - the 1x1 projection shortcut is appended as whole reduction steps of its own;
+//   - LDS fragment reads of sub-step ks+1 are issued before the MFMAs of sub-step ks;
+//   - MFMA shape is a template parameter: 32x32x2 for the wide contractions, 16x16x4 for
+//     the skinny ones (auxiliary heads with at most 16 filters).
+#include "nf_internal.h"
+
+namespace nf {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+constexpr int BK = 32;
+constexpr int LDK = BK + 4;
+constexpr int NTHREADS = 256;
+constexpr int OOB = (int)0x80000000;      // offset no buffer of < 2 GiB contains
+constexpr int RSRC_FLAGS = 0x00020000;    // raw buffer, 32-bit data format
+
+struct FastAux {
+  FastDiv div_c, div_s;
+  uint32_t x_bytes, w_bytes, xs_bytes, wp_bytes;
+  int nkb_conv, nkb_proj;
+};
+
+__device__ inline float4 bload(__amdgpu_buffer_rsrc_t r, int voff) {
+  const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+
+template <int MF>
+struct Mfma;
+template <>
+struct Mfma<32> {
+  typedef floatx16 acc_t;
+  static constexpr int NACC = 16, KSTEP = 8;  // k covered by one 16-byte fragment read
+  static __device__ inline acc_t run(float a, float b, acc_t c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+  // row of accumulator element e for lane group g (= lane / 32)
+  static __device__ inline int row(int e, int g) { return 8 * (e >> 2) + 4 * g + (e & 3); }
+};
+template <>
+struct Mfma<16> {
+  typedef floatx4 acc_t;
+  static constexpr int NACC = 4, KSTEP = 16;
+  static __device__ inline acc_t run(float a, float b, acc_t c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+  static __device__ inline int row(int e, int g) { return 4 * g + e; }  // g = lane / 16
+};
+
+template <int BM, int BN, int WM, int WN, int MF>
+__global__ __launch_bounds__(NTHREADS) void igemm_fwd_fast_kernel(FwdProblem p, FastAux q) {
+  using MM = Mfma<MF>;
+  using acc_t = typename MM::acc_t;
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int MT = TM / MF, NT = TN / MF;
+  constexpr int PA = BM / 32, PB = (BN + 31) / 32;
+  constexpr int NKS = BK / MM::KSTEP;
+  static_assert(WM * WN == 4 && MT >= 1 && NT >= 1 && BM % 32 == 0, "tile");
+
+  __shared__ __attribute__((aligned(16))) float As[2][BM][LDK];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BN][LDK];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int j = lane % MF, g = lane / MF;  // row/column inside an MFMA tile, k group
+
+  const int tiles_n = (p.N + BN - 1) / BN;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, q.x_bytes, RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, q.w_bytes, RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t rxs = __builtin_amdgcn_make_buffer_rsrc((void *)p.xs, 0, q.xs_bytes, RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t rwp = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, q.wp_bytes, RSRC_FLAGS);
+
+  // ---- per-thread gather state: chunk `ch` (4 consecutive kg) of rows row0 + 32*i ----
+  const int ch = t & 7, row0 = t >> 3;
+  int abase[PA], sbase[PA];
+  uint32_t amask[PA];
+#pragma unroll
+  for (int i = 0; i < PA; ++i) {
+    const int m = m0 + row0 + 32 * i;
+    abase[i] = 0, sbase[i] = OOB, amask[i] = 0;
+    if (m < p.M) {
+      const int img = (int)p.div_howo.div((uint32_t)m);
+      const int rem = m - img * p.Ho * p.Wo;
+      const int ho = (int)p.div_wo.div((uint32_t)rem);
+      const int wo = rem - ho * p.Wo;
+      const int hi0 = ho * p.stride - p.pad, wi0 = wo * p.stride - p.pad;
+      abase[i] = ((img * p.H + hi0) * p.W + wi0) * p.C * 4;  // may point before the image: used only with a valid tap
+      uint32_t mask = 0;
+      for (int r = 0; r < p.R; ++r)
+        for (int s = 0; s < p.S; ++s)
+          if ((unsigned)(hi0 + r) < (unsigned)p.H && (unsigned)(wi0 + s) < (unsigned)p.W) mask |= 1u << (r * p.S + s);
+      amask[i] = mask;
+      if (q.nkb_proj) sbase[i] = ((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs * 4;
+    }
+  }
+  int bbase[PB], pbase[PB];
+#pragma unroll
+  for (int i = 0; i < PB; ++i) {
+    const int n = n0 + row0 + 32 * i;
+    const bool ok = n < p.N && (row0 + 32 * i) < BN;
+    bbase[i] = ok ? n * p.RSC * 4 : OOB;
+    pbase[i] = ok ? n * p.Cs * 4 : OOB;
+  }
+
+  float4 ra[PA], rb[PB];
+  const int nkb = q.nkb_conv + q.nkb_proj;
+
+  auto gload = [&](int kb) {
+    if (kb < q.nkb_conv) {  // uniform across the workgroup
+      const int kg = kb * BK + ch * 4;
+      const bool in = kg < p.RSC;
+      const int tap = in ? (int)q.div_c.div((uint32_t)kg) : 0;
+      const int c = kg - tap * p.C;
+      const int r = (int)q.div_s.div((uint32_t)tap);
+      const int s = tap - r * p.S;
+      const int toff = ((r * p.W + s) * p.C + c) * 4;
+#pragma unroll
+      for (int i = 0; i < PA; ++i) {
+        const bool ok = in && ((amask[i] >> tap) & 1u);
+        ra[i] = bload(rx, ok ? abase[i] + toff : OOB);
+      }
+#pragma unroll
+      for (int i = 0; i < PB; ++i) {
+        const bool ok = in && bbase[i] != OOB;
+        rb[i] = bload(rw, ok ? bbase[i] + kg * 4 : OOB);
+      }
+    } else {
+      const int c = (kb - q.nkb_conv) * BK + ch * 4;
+      const bool in = c < p.Cs;
+#pragma unroll
+      for (int i = 0; i < PA; ++i) ra[i] = bload(rxs, (in && sbase[i] != OOB) ? sbase[i] + c * 4 : OOB);
+#pragma unroll
+      for (int i = 0; i < PB; ++i) rb[i] = bload(rwp, (in && pbase[i] != OOB) ? pbase[i] + c * 4 : OOB);
+    }
+  };
+
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[buf][row0 + 32 * i][ch * 4]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i)
+      if (BN >= 32 * (i + 1) || row0 + 32 * i < BN)
+        *reinterpret_cast<float4 *>(&Bs[buf][row0 + 32 * i][ch * 4]) = rb[i];
+  };
+
+  acc_t acc[MT][NT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b)
+#pragma unroll
+      for (int e = 0; e < MM::NACC; ++e) acc[a][b][e] = 0.f;
+
+  gload(0);
+  lstore(0);
+  __syncthreads();
+
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int cur = kb & 1;
+    const bool more = kb + 1 < nkb;
+    if (more) gload(kb + 1);
+
+    float4 af[2][MT], bf[2][NT];
+    auto lfrag = [&](int ks, int slot) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+        af[slot][a] = *reinterpret_cast<const float4 *>(&As[cur][wm * TM + a * MF + j][ks * MM::KSTEP + g * 4]);
+#pragma unroll
+      for (int b = 0; b < NT; ++b)
+        bf[slot][b] = *reinterpret_cast<const float4 *>(&Bs[cur][wn * TN + b * MF + j][ks * MM::KSTEP + g * 4]);
+    };
+    lfrag(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const int slot = ks & 1;
+      if (ks + 1 < NKS) lfrag(ks + 1, slot ^ 1);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+          for (int b = 0; b < NT; ++b) {
+            const float av = kk == 0 ? af[slot][a].x : kk == 1 ? af[slot][a].y : kk == 2 ? af[slot][a].z : af[slot][a].w;
+            const float bv = kk == 0 ? bf[slot][b].x : kk == 1 ? bf[slot][b].y : kk == 2 ? bf[slot][b].z : bf[slot][b].w;
+            acc[a][b] = MM::run(av, bv, acc[a][b]);
+          }
+      }
+    }
+    if (more) lstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: bias, identity shortcut, ReLU, mask; consecutive lanes store consecutive n ----
+#pragma unroll
+  for (int b = 0; b < NT; ++b) {
+    const int n = n0 + wn * TN + b * MF + j;
+    if (n >= p.N) continue;
+    const float bias = p.bias ? p.bias[n] : 0.f;
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+#pragma unroll
+      for (int e = 0; e < MM::NACC; ++e) {
+        const int m = m0 + wm * TM + a * MF + MM::row(e, g);
+        if (m >= p.M) continue;
+        const long long o = (long long)m * p.N + n;
+        float v = acc[a][b][e] + bias;
+        if (p.addsrc) v += p.addsrc[o];
+        if (p.relu) v = v > 0.f ? v : 0.f;
+        if (p.mask) v = p.mask[o] > 0.f ? v : 0.f;
+        p.out[o] = v;
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int MF>
+hipError_t launch_cfg(const FwdProblem &p, const FastAux &q, hipStream_t st) {
+  const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, WM, WN, MF>), dim3(tiles), dim3(NTHREADS), 0, st, p, q);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool igemm_fwd_fast_applicable(const FwdProblem &p) {
+  const long long lim = 0x7FFFFFF0ll;
+  const long long B = p.M / ((long long)p.Ho * p.Wo);
+  if (p.C % 4 || p.Cs % 4 || p.R * p.S > 32) return false;
+  if (B * p.H * p.W * p.C * 4 > lim || (long long)p.N * p.RSC * 4 > lim) return false;
+  if (p.Cs && (B * p.Hs * p.Ws * p.Cs * 4 > lim || (long long)p.N * p.Cs * 4 > lim)) return false;
+  return true;
+}
+
+hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char **kernel) {
+  FastAux q;
+  const long long B = p.M / ((long long)p.Ho * p.Wo);
+  q.div_c = FastDiv(p.C), q.div_s = FastDiv(p.S);
+  q.x_bytes = (uint32_t)(B * p.H * p.W * p.C * 4);
+  q.w_bytes = (uint32_t)((long long)p.N * p.RSC * 4);
+  q.xs_bytes = p.Cs ? (uint32_t)(B * p.Hs * p.Ws * p.Cs * 4) : 0;
+  q.wp_bytes = p.Cs ? (uint32_t)((long long)p.N * p.Cs * 4) : 0;
+  q.nkb_conv = (p.RSC + BK - 1) / BK;
+  q.nkb_proj = p.Cs ? (p.Cs + BK - 1) / BK : 0;
+  if (p.N > 64) {
+    *kernel = "igemm_fwd_fast_128x128";
+    return launch_cfg<128, 128, 2, 2, 32>(p, q, st);
+  }
+  if (p.N > 32) {
+    *kernel = "igemm_fwd_fast_128x64";
+    return launch_cfg<128, 64, 2, 2, 32>(p, q, st);
+  }
+  if (p.N > 16) {
+    *kernel = "igemm_fwd_fast_128x32";
+    return launch_cfg<128, 32, 4, 1, 32>(p, q, st);
+  }
+  *kernel = "igemm_fwd_fast_64x16";
+  return launch_cfg<64, 16, 4, 1, 16>(p, q, st);
+}
+
+}  // namespace nf

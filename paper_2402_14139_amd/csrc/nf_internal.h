@@ -39,6 +39,9 @@ struct FwdProblem {
 };
 // `*kernel` receives a static string naming the tile configuration that was launched
 hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **kernel);
+// branch-free buffer-load variant (igemm_fwd_fast.hip); launch_igemm_fwd picks it when applicable
+bool igemm_fwd_fast_applicable(const FwdProblem &p);
+hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char **kernel);
 
 // ---- implicit-GEMM weight gradient: part[z][p][q] = sum_{m in split z} d[m][p] * col(x)[m][q]
 struct WgradProblem {
