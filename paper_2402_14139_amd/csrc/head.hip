@@ -116,34 +116,48 @@ __global__ __launch_bounds__(HT) void loss_mean_kernel(const float *__restrict__
 }
 
 // gamma_n backward in one launch:
-//   blocks [0, nb_w)            dWf[q][f] = sum_n dz[n][q] * Pq[n][f]
-//   blocks [nb_w, nb_w+nb_p)    dPq[n][f] = sum_q dz[n][q] * Wf[q][f]
-//   blocks [.., +nb_b)          dbf[q]    = sum_n dz[n][q]
+//   blocks [0, nb_w)          one class q and one chunk of `fch` features: the 256 threads are
+//                             fch feature lanes x (256/fch) batch slices; slice sums are added in
+//                             order through LDS.  dWf[q][f] = sum_n dz[n][q] * Pq[n][f];
+//                             chunk 0 also forms dbf[q] = sum_n dz[n][q].
+//   blocks [nb_w, nb_w+nb_p)  dPq[n][f] = sum_q dz[n][q] * Wf[q][f], one thread per element
 __global__ __launch_bounds__(HT) void fc_bwd_kernel(HeadShape s, const float *__restrict__ Pq,
                                                     const float *__restrict__ dz, const float *__restrict__ Wf,
                                                     float *__restrict__ dWf, float *__restrict__ dbf,
-                                                    float *__restrict__ dPq, int nb_w, int nb_p) {
+                                                    float *__restrict__ dPq, int nb_w, int fch, int nchunks) {
+  __shared__ float red[HT];
+  __shared__ float redb[HT];
   const int b = blockIdx.x, t = threadIdx.x;
   if (b < nb_w) {
-    const long long i = (long long)b * HT + t;
-    if (i >= (long long)s.Cls * s.F) return;
-    const int q = (int)(i / s.F), f = (int)(i - (long long)q * s.F);
-    float acc = 0.f;
-    for (int n = 0; n < s.B; ++n) acc += dz[(long long)n * s.Cls + q] * Pq[(long long)n * s.F + f];
-    dWf[i] = acc;
-  } else if (b < nb_w + nb_p) {
+    const int q = b / nchunks, chunk = b - q * nchunks;
+    const int fl = t % fch, ns = t / fch, NS = HT / fch;
+    const int f = chunk * fch + fl;
+    float acc = 0.f, bsum = 0.f;
+    if (f < s.F) {
+      for (int n = ns; n < s.B; n += NS) {
+        const float d = dz[(long long)n * s.Cls + q];
+        bsum += d;
+        acc += d * Pq[(long long)n * s.F + f];
+      }
+    }
+    red[t] = acc;
+    redb[t] = bsum;
+    __syncthreads();
+    if (ns == 0 && f < s.F) {
+      for (int k = 1; k < NS; ++k) acc += red[k * fch + fl];
+      dWf[(long long)q * s.F + f] = acc;
+    }
+    if (t == 0 && chunk == 0) {
+      for (int k = 1; k < NS; ++k) bsum += redb[k * fch];
+      dbf[q] = bsum;
+    }
+  } else {
     const long long i = (long long)(b - nb_w) * HT + t;
     if (i >= (long long)s.B * s.F) return;
     const int n = (int)(i / s.F), f = (int)(i - (long long)n * s.F);
     float acc = 0.f;
     for (int q = 0; q < s.Cls; ++q) acc += dz[(long long)n * s.Cls + q] * Wf[(long long)q * s.F + f];
     dPq[i] = acc;
-  } else {
-    const int q = (b - nb_w - nb_p) * HT + t;
-    if (q >= s.Cls) return;
-    float acc = 0.f;
-    for (int n = 0; n < s.B; ++n) acc += dz[(long long)n * s.Cls + q];
-    dbf[q] = acc;
   }
 }
 
@@ -195,11 +209,13 @@ hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStre
 
 hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, const float *Wf, float *dWf,
                          float *dbf, float *dPq, hipStream_t st) {
-  const int nb_w = (int)(((long long)h.Cls * h.F + HT - 1) / HT);
+  int fch = 16;
+  while (fch < 64 && fch < h.F) fch *= 2;
+  const int nchunks = (h.F + fch - 1) / fch;
+  const int nb_w = h.Cls * nchunks;
   const int nb_p = (int)(((long long)h.B * h.F + HT - 1) / HT);
-  const int nb_b = (h.Cls + HT - 1) / HT;
-  hipLaunchKernelGGL(fc_bwd_kernel, dim3(nb_w + nb_p + nb_b), dim3(HT), 0, st, h, Pq, dz, Wf, dWf, dbf, dPq, nb_w,
-                     nb_p);
+  hipLaunchKernelGGL(fc_bwd_kernel, dim3(nb_w + nb_p), dim3(HT), 0, st, h, Pq, dz, Wf, dWf, dbf, dPq, nb_w, fch,
+                     nchunks);
   return hipGetLastError();
 }
 

@@ -22,6 +22,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BKM = 32;  // reduction rows staged per step
 constexpr int NTHREADS = 256;
+constexpr int OOB = (int)0x80000000;    // offset no buffer of < 2 GiB contains
+constexpr int RSRC_FLAGS = 0x00020000;  // raw buffer, 32-bit data format
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ inline float4 bload(__amdgpu_buffer_rsrc_t r, int voff) {
+  const floatx4 v = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
 
 template <int N>
 struct VecLoad;
@@ -45,7 +53,10 @@ struct VecLoad<4> {
 };
 
 // BP x BQ output tile, WP x WQ waves, each wave (32*PT) x (32*QT).
-template <int BP, int BQ, int WP, int WQ, int VEC>
+// BUF (needs VEC == 4 and operands < 2 GiB): global reads are raw buffer loads and every
+// "no data here" case (row past the split, tap outside the image, column past P or Q) is an
+// out-of-range offset that the hardware answers with zeros -- no branches in the gather.
+template <int BP, int BQ, int WP, int WQ, int VEC, bool BUF>
 __global__ __launch_bounds__(NTHREADS) void igemm_wgrad_kernel(WgradProblem p) {
   constexpr int TP = BP / WP, TQ = BQ / WQ;
   constexpr int PT = TP / 32, QT = TQ / 32;
@@ -93,7 +104,38 @@ __global__ __launch_bounds__(NTHREADS) void igemm_wgrad_kernel(WgradProblem p) {
   float4 bsum = make_float4(0.f, 0.f, 0.f, 0.f);
   const bool do_bias = (blockIdx.x == 0) && (p.part_b != nullptr);
 
+  const __amdgpu_buffer_rsrc_t rsd = __builtin_amdgcn_make_buffer_rsrc((void *)p.d, 0, p.d_bytes, RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, RSRC_FLAGS);
+  const __amdgpu_buffer_rsrc_t rsxs = __builtin_amdgcn_make_buffer_rsrc((void *)p.xs, 0, p.xs_bytes, RSRC_FLAGS);
+  const int dcol_off = pcol < p.P ? pcol * 4 : OOB;  // byte offset of this thread's D columns
+  const int xtap_off = ((qr[0] * p.W + qs[0]) * p.C + qc[0]) * 4;
+
   auto gload = [&](int mb) {
+    if constexpr (BUF) {
+#pragma unroll
+      for (int i = 0; i < NP; ++i) {
+        const int m = mb + rowp + RP * i;
+        const bool ok = m < m_end && dcol_off != OOB;
+        rd[i] = bload(rsd, ok ? m * p.P * 4 + dcol_off : OOB);
+      }
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        const int m = mb + rowq + RQ * i;
+        const int img = (int)p.div_howo.div((uint32_t)m);
+        const int rem = m - img * p.Ho * p.Wo;
+        const int ho = (int)p.div_wo.div((uint32_t)rem);
+        const int wo = rem - ho * p.Wo;
+        if (qkind[0] == 0) {  // fixed per thread
+          const int hi0 = ho * p.stride - p.pad, wi0 = wo * p.stride - p.pad;
+          const bool ok = m < m_end && (unsigned)(hi0 + qr[0]) < (unsigned)p.H && (unsigned)(wi0 + qs[0]) < (unsigned)p.W;
+          rx[i] = bload(rsx, ok ? ((img * p.H + hi0) * p.W + wi0) * p.C * 4 + xtap_off : OOB);
+        } else {
+          const bool ok = m < m_end && qkind[0] == 1;
+          rx[i] = bload(rsxs, ok ? (((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs + qc[0]) * 4 : OOB);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int m = mb + rowp + RP * i;
@@ -221,25 +263,55 @@ __global__ __launch_bounds__(NTHREADS) void igemm_wgrad_kernel(WgradProblem p) {
   }
 }
 
-__global__ void wgrad_reduce_kernel(const float *__restrict__ part, const float *__restrict__ part_b, int splits,
-                                    int P, int Q, int Qld, int Q0, float *__restrict__ out0,
-                                    float *__restrict__ out1, float *__restrict__ ob) {
-  const long long total = (long long)P * Q;
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < total) {
-    const int pr = (int)(i / Q), q = (int)(i - (long long)pr * Q);
-    const float *src = part + (long long)pr * Qld + q;
-    float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += src[(long long)z * P * Qld];
-    if (q < Q0)
-      out0[(long long)pr * Q0 + q] = s;
-    else
-      out1[(long long)pr * (Q - Q0) + (q - Q0)] = s;
-  } else if (ob && i < total + P) {
-    const int pr = (int)(i - total);
-    float s = 0.f;
-    for (int z = 0; z < splits; ++z) s += part_b[(long long)z * P + pr];
-    ob[pr] = s;
+// Sum of the split partials in a fixed order.  A workgroup owns 256/ZS groups of four
+// consecutive elements of the flattened [P][Qld] tile array; its ZS thread rows each add every
+// ZS-th split with 16-byte loads, then the ZS row sums are added in order through LDS.  The
+// last workgroup does the same for the bias partials.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part,
+                                                           const float *__restrict__ part_b, int splits, int P, int Q,
+                                                           int Qld, int Q0, float *__restrict__ out0,
+                                                           float *__restrict__ out1, float *__restrict__ ob, int ZS,
+                                                           int main_blocks) {
+  __shared__ float4 red[256];
+  const int t = threadIdx.x;
+  const int cols = 256 / ZS;
+  const int col = t % cols, zs = t / cols;
+  if ((int)blockIdx.x < main_blocks) {
+    const long long n4 = ((long long)P * Qld) >> 2;  // Qld is a multiple of 4
+    const long long i4 = (long long)blockIdx.x * cols + col;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i4 < n4) {
+      const float4 *src = reinterpret_cast<const float4 *>(part) + i4;
+      for (int z = zs; z < splits; z += ZS) {
+        const float4 v = src[(long long)z * n4];
+        s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+      }
+    }
+    red[t] = s;
+    __syncthreads();
+    if (zs == 0 && i4 < n4) {
+      for (int k = 1; k < ZS; ++k) {
+        const float4 v = red[k * cols + col];
+        s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+      }
+      const long long e = i4 << 2;
+      const int pr = (int)(e / Qld), q = (int)(e - (long long)pr * Qld);
+      const float vals[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int qq = q + k;
+        if (qq < Q0)
+          out0[(long long)pr * Q0 + qq] = vals[k];
+        else if (qq < Q)
+          out1[(long long)pr * (Q - Q0) + (qq - Q0)] = vals[k];
+      }
+    }
+  } else if (ob) {
+    for (int pr = t; pr < P; pr += 256) {
+      float sb = 0.f;
+      for (int z = 0; z < splits; ++z) sb += part_b[(long long)z * P + pr];
+      ob[pr] = sb;
+    }
   }
 }
 
@@ -253,12 +325,19 @@ inline TileChoice pick_tile(int P) {
 }
 
 template <int BP, int BQ, int WP, int WQ>
-hipError_t launch_cfg(const WgradProblem &p, bool vec, hipStream_t st) {
+hipError_t launch_cfg(const WgradProblem &p0, bool vec, hipStream_t st) {
+  WgradProblem p = p0;
   dim3 grid((p.Q + BQ - 1) / BQ, (p.P + BP - 1) / BP, p.splits);
-  if (vec)
-    hipLaunchKernelGGL((igemm_wgrad_kernel<BP, BQ, WP, WQ, 4>), grid, dim3(NTHREADS), 0, st, p);
-  else
-    hipLaunchKernelGGL((igemm_wgrad_kernel<BP, BQ, WP, WQ, 1>), grid, dim3(NTHREADS), 0, st, p);
+  const long long lim = 0x7FFFFFF0ll, B = p.M / ((long long)p.Ho * p.Wo);
+  const long long db = (long long)p.M * p.P * 4, xb = B * p.H * p.W * p.C * 4, xsb = p.Cs ? B * p.Hs * p.Ws * p.Cs * 4 : 0;
+  if (vec && db <= lim && xb <= lim && xsb <= lim) {
+    p.d_bytes = (uint32_t)db, p.x_bytes = (uint32_t)xb, p.xs_bytes = (uint32_t)xsb;
+    hipLaunchKernelGGL((igemm_wgrad_kernel<BP, BQ, WP, WQ, 4, true>), grid, dim3(NTHREADS), 0, st, p);
+  } else if (vec) {
+    hipLaunchKernelGGL((igemm_wgrad_kernel<BP, BQ, WP, WQ, 4, false>), grid, dim3(NTHREADS), 0, st, p);
+  } else {
+    hipLaunchKernelGGL((igemm_wgrad_kernel<BP, BQ, WP, WQ, 1, false>), grid, dim3(NTHREADS), 0, st, p);
+  }
   return hipGetLastError();
 }
 
@@ -267,12 +346,13 @@ hipError_t launch_cfg(const WgradProblem &p, bool vec, hipStream_t st) {
 int wgrad_pick_splits(int P, int Q, int M) {
   const TileChoice tc = pick_tile(P);
   const long long tiles = (long long)((P + tc.BP - 1) / tc.BP) * ((Q + tc.BQ - 1) / tc.BQ);
-  // aim at ~4 workgroups per compute unit (256 CUs), keep at least 4 staging steps per split
-  long long want = (1024 + tiles - 1) / tiles;
+  // Two workgroups fit on a compute unit (LDS), 256 CUs: aim at <= 512 workgroups that are all
+  // resident at once, and keep at least 4 staging steps per split.  Every workgroup writes its
+  // tile once, so fewer splits also means less partial-sum traffic.
+  long long want = 512 / tiles;
   const long long max_by_m = (M + 4 * BKM - 1) / (4 * BKM);
   if (want > max_by_m) want = max_by_m;
   if (want < 1) want = 1;
-  if (want > 512) want = 512;
   return (int)want;
 }
 
@@ -292,11 +372,13 @@ hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char 
 
 hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int splits, int P, int Q, int Qld,
                                int Q0, float *out0, float *out1, float *ob, hipStream_t st) {
-  const long long total = (long long)P * Q + (ob ? P : 0);
-  const int threads = 256;
-  const long long blocks = (total + threads - 1) / threads;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)blocks), dim3(threads), 0, st, part, part_b, splits, P, Q,
-                     Qld, Q0, out0, out1, ob);
+  int ZS = 1;
+  while (ZS < 16 && ZS < splits) ZS *= 2;
+  const int cols = 256 / ZS;
+  const long long n4 = ((long long)P * Qld) / 4;
+  const int main_blocks = (int)((n4 + cols - 1) / cols);
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)(main_blocks + (ob ? 1 : 0))), dim3(256), 0, st, part, part_b,
+                     splits, P, Q, Qld, Q0, out0, out1, ob, ZS, main_blocks);
   return hipGetLastError();
 }
 

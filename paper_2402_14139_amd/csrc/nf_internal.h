@@ -53,6 +53,7 @@ struct WgradProblem {
   int P, M, RSC, Q, Qld;
   int splits, m_per_split;
   FastDiv div_howo, div_wo;
+  uint32_t d_bytes, x_bytes, xs_bytes;  // filled by the launcher for the buffer-load variant
 };
 // chooses the tile shape for (P,Q); reports how many splits of M it wants
 int wgrad_pick_splits(int P, int Q, int M);
