@@ -13,6 +13,8 @@
 //   - LDS fragment reads of sub-step ks+1 are issued before the MFMAs of sub-step ks;
 //   - MFMA shape is a template parameter: 32x32x2 for the wide contractions, 16x16x4 for
 //     the skinny ones (auxiliary heads with at most 16 filters).
+#include <type_traits>
+
 #include "nf_internal.h"
 
 namespace nf {
@@ -24,7 +26,6 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 32;
 constexpr int LDK = BK + 4;
-constexpr int NTHREADS = 256;
 constexpr int OOB = (int)0x80000000;      // offset no buffer of < 2 GiB contains
 constexpr int RSRC_FLAGS = 0x00020000;    // raw buffer, 32-bit data format
 
@@ -57,15 +58,17 @@ struct Mfma<16> {
   static __device__ inline int row(int e, int g) { return 4 * g + e; }  // g = lane / 16
 };
 
-template <int BM, int BN, int WM, int WN, int MF>
-__global__ __launch_bounds__(NTHREADS) void igemm_fwd_fast_kernel(FwdProblem p, FastAux q) {
+template <int BM, int BN, int WM, int WN, int MF, bool PROJ, bool SCHED>
+__global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem p, FastAux q) {
   using MM = Mfma<MF>;
   using acc_t = typename MM::acc_t;
+  constexpr int NTHREADS = WM * WN * 64;
+  constexpr int RPP = NTHREADS / 8;  // rows staged per pass (8 threads cover one row of BK floats)
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MT = TM / MF, NT = TN / MF;
-  constexpr int PA = BM / 32, PB = (BN + 31) / 32;
+  constexpr int PA = BM / RPP, PB = (BN + RPP - 1) / RPP;
   constexpr int NKS = BK / MM::KSTEP;
-  static_assert(WM * WN == 4 && MT >= 1 && NT >= 1 && BM % 32 == 0, "tile");
+  static_assert(MT >= 1 && NT >= 1 && BM % RPP == 0, "tile");
 
   __shared__ __attribute__((aligned(16))) float As[2][BM][LDK];
   __shared__ __attribute__((aligned(16))) float Bs[2][BN][LDK];
@@ -84,13 +87,13 @@ __global__ __launch_bounds__(NTHREADS) void igemm_fwd_fast_kernel(FwdProblem p, 
   const __amdgpu_buffer_rsrc_t rxs = __builtin_amdgcn_make_buffer_rsrc((void *)p.xs, 0, q.xs_bytes, RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t rwp = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, q.wp_bytes, RSRC_FLAGS);
 
-  // ---- per-thread gather state: chunk `ch` (4 consecutive kg) of rows row0 + 32*i ----
+  // ---- per-thread gather state: chunk `ch` (4 consecutive kg) of rows row0 + RPP*i ----
   const int ch = t & 7, row0 = t >> 3;
   int abase[PA], sbase[PA];
   uint32_t amask[PA];
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
-    const int m = m0 + row0 + 32 * i;
+    const int m = m0 + row0 + RPP * i;
     abase[i] = 0, sbase[i] = OOB, amask[i] = 0;
     if (m < p.M) {
       const int img = (int)p.div_howo.div((uint32_t)m);
@@ -110,51 +113,62 @@ __global__ __launch_bounds__(NTHREADS) void igemm_fwd_fast_kernel(FwdProblem p, 
   int bbase[PB], pbase[PB];
 #pragma unroll
   for (int i = 0; i < PB; ++i) {
-    const int n = n0 + row0 + 32 * i;
-    const bool ok = n < p.N && (row0 + 32 * i) < BN;
+    const int n = n0 + row0 + RPP * i;
+    const bool ok = n < p.N && (row0 + RPP * i) < BN;
     bbase[i] = ok ? n * p.RSC * 4 : OOB;
     pbase[i] = ok ? n * p.Cs * 4 : OOB;
   }
 
-  float4 ra[PA], rb[PB];
+  // Two register sets of staged chunks: global loads run two reduction steps ahead of the MFMAs.
+  float4 ra[2][PA], rb[2][PB];
   const int nkb = q.nkb_conv + q.nkb_proj;
 
-  auto gload = [&](int kb) {
-    if (kb < q.nkb_conv) {  // uniform across the workgroup
-      const int kg = kb * BK + ch * 4;
-      const bool in = kg < p.RSC;
-      const int tap = in ? (int)q.div_c.div((uint32_t)kg) : 0;
-      const int c = kg - tap * p.C;
-      const int r = (int)q.div_s.div((uint32_t)tap);
-      const int s = tap - r * p.S;
-      const int toff = ((r * p.W + s) * p.C + c) * 4;
+  // Branch-free gather of step kb into register set `set`.  Steps past the end, the padding of the
+  // reduction axis, taps outside the image and rows past M or N all become the out-of-range
+  // offset.  The projection steps (kb >= nkb_conv) read the shortcut tensor and its 1x1 filter
+  // through a uniform select of the buffer descriptor.
+  auto gload = [&](int kb, int set) {
+    const int kg = kb * BK + ch * 4;
+    const bool in = kg < p.RSC;
+    const int tap = in ? (int)q.div_c.div((uint32_t)kg) : 0;
+    const int c = kg - tap * p.C;
+    const int r = (int)q.div_s.div((uint32_t)tap);
+    const int sx = tap - r * p.S;
+    const int toff = ((r * p.W + sx) * p.C + c) * 4;
+    int offa[PA], offb[PB];
 #pragma unroll
-      for (int i = 0; i < PA; ++i) {
-        const bool ok = in && ((amask[i] >> tap) & 1u);
-        ra[i] = bload(rx, ok ? abase[i] + toff : OOB);
+    for (int i = 0; i < PA; ++i) offa[i] = (in && ((amask[i] >> tap) & 1u)) ? abase[i] + toff : OOB;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) offb[i] = (in && bbase[i] != OOB) ? bbase[i] + kg * 4 : OOB;
+    if constexpr (PROJ) {
+      const bool is_proj = kb >= q.nkb_conv;  // uniform
+      const int cp = (kb - q.nkb_conv) * BK + ch * 4;
+      const bool inp = is_proj && cp < p.Cs;
+#pragma unroll
+      for (int i = 0; i < PA; ++i) offa[i] = is_proj ? ((inp && sbase[i] != OOB) ? sbase[i] + cp * 4 : OOB) : offa[i];
+#pragma unroll
+      for (int i = 0; i < PB; ++i) offb[i] = is_proj ? ((inp && pbase[i] != OOB) ? pbase[i] + cp * 4 : OOB) : offb[i];
+      if (is_proj) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i) ra[set][i] = bload(rxs, offa[i]);
+#pragma unroll
+        for (int i = 0; i < PB; ++i) rb[set][i] = bload(rwp, offb[i]);
+        return;
       }
-#pragma unroll
-      for (int i = 0; i < PB; ++i) {
-        const bool ok = in && bbase[i] != OOB;
-        rb[i] = bload(rw, ok ? bbase[i] + kg * 4 : OOB);
-      }
-    } else {
-      const int c = (kb - q.nkb_conv) * BK + ch * 4;
-      const bool in = c < p.Cs;
-#pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = bload(rxs, (in && sbase[i] != OOB) ? sbase[i] + c * 4 : OOB);
-#pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i] = bload(rwp, (in && pbase[i] != OOB) ? pbase[i] + c * 4 : OOB);
     }
+#pragma unroll
+    for (int i = 0; i < PA; ++i) ra[set][i] = bload(rx, offa[i]);
+#pragma unroll
+    for (int i = 0; i < PB; ++i) rb[set][i] = bload(rw, offb[i]);
   };
 
-  auto lstore = [&](int buf) {
+  auto lstore = [&](int buf, int set) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[buf][row0 + 32 * i][ch * 4]) = ra[i];
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<float4 *>(&As[buf][row0 + RPP * i][ch * 4]) = ra[set][i];
 #pragma unroll
     for (int i = 0; i < PB; ++i)
-      if (BN >= 32 * (i + 1) || row0 + 32 * i < BN)
-        *reinterpret_cast<float4 *>(&Bs[buf][row0 + 32 * i][ch * 4]) = rb[i];
+      if (BN >= RPP * (i + 1) || row0 + RPP * i < BN)
+        *reinterpret_cast<float4 *>(&Bs[buf][row0 + RPP * i][ch * 4]) = rb[set][i];
   };
 
   acc_t acc[MT][NT];
@@ -165,43 +179,85 @@ __global__ __launch_bounds__(NTHREADS) void igemm_fwd_fast_kernel(FwdProblem p, 
 #pragma unroll
       for (int e = 0; e < MM::NACC; ++e) acc[a][b][e] = 0.f;
 
-  gload(0);
-  lstore(0);
-  __syncthreads();
-
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int cur = kb & 1;
-    const bool more = kb + 1 < nkb;
-    if (more) gload(kb + 1);
-
-    float4 af[2][MT], bf[2][NT];
-    auto lfrag = [&](int ks, int slot) {
+  float4 af[2][MT], bf[2][NT];
+  auto lfrag = [&](int buf, int ks, int slot) {
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+      af[slot][a] = *reinterpret_cast<const float4 *>(&As[buf][wm * TM + a * MF + j][ks * MM::KSTEP + g * 4]);
+#pragma unroll
+    for (int b = 0; b < NT; ++b)
+      bf[slot][b] = *reinterpret_cast<const float4 *>(&Bs[buf][wn * TN + b * MF + j][ks * MM::KSTEP + g * 4]);
+  };
+  auto mma = [&](int slot) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
       for (int a = 0; a < MT; ++a)
-        af[slot][a] = *reinterpret_cast<const float4 *>(&As[cur][wm * TM + a * MF + j][ks * MM::KSTEP + g * 4]);
 #pragma unroll
-      for (int b = 0; b < NT; ++b)
-        bf[slot][b] = *reinterpret_cast<const float4 *>(&Bs[cur][wn * TN + b * MF + j][ks * MM::KSTEP + g * 4]);
-    };
-    lfrag(0, 0);
+        for (int b = 0; b < NT; ++b) {
+          const float av = kk == 0 ? af[slot][a].x : kk == 1 ? af[slot][a].y : kk == 2 ? af[slot][a].z : af[slot][a].w;
+          const float bv = kk == 0 ? bf[slot][b].x : kk == 1 ? bf[slot][b].y : kk == 2 ? bf[slot][b].z : bf[slot][b].w;
+          acc[a][b] = MM::run(av, bv, acc[a][b]);
+        }
+    }
+  };
+  static_assert(NKS % 2 == 0, "fragment slots alternate per sub-step");
+
+  // ---- software pipeline ------------------------------------------------------------------
+  // Step kb (LDS buffer kb&1):
+  //   sub-steps 0..NKS-2: fragment reads of sub-step ks+1 ride on the first MFMAs of sub-step ks;
+  //     the address arithmetic and the buffer loads of step kb+2 are spread between the MFMAs of
+  //     the first sub-steps; the LDS writes of step kb+1 (loaded one step ago) ride on the MFMAs
+  //     of sub-step NKS-2;
+  //   barrier; first fragments of step kb+1; MFMAs of the last sub-step.
+  // One barrier per step, and no instruction class waits for the MFMA pipe to drain.
+  constexpr int NM = 4 * MT * NT;   // MFMAs per sub-step
+  constexpr int NR = MT + NT;       // fragment reads per sub-step
+  constexpr int NV = PA + PB;       // buffer loads (and LDS writes) per step
+  auto step = [&](int kb, auto par_tag) {
+    constexpr int par = decltype(par_tag)::value;
+    gload(kb + 2, par);  // set `par` held step kb, already in LDS
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const int slot = ks & 1;
-      if (ks + 1 < NKS) lfrag(ks + 1, slot ^ 1);
+    for (int ks = 0; ks + 1 < NKS; ++ks) {
+      lfrag(par, ks + 1, (ks + 1) & 1);
+      mma(ks & 1);
+    }
+    lstore(par ^ 1, par ^ 1);  // step kb+1
+    if constexpr (SCHED) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
+      for (int ks = 0; ks + 1 < NKS; ++ks) {
+        const bool first = ks == 0, last = ks + 2 == NKS;
 #pragma unroll
-        for (int a = 0; a < MT; ++a)
-#pragma unroll
-          for (int b = 0; b < NT; ++b) {
-            const float av = kk == 0 ? af[slot][a].x : kk == 1 ? af[slot][a].y : kk == 2 ? af[slot][a].z : af[slot][a].w;
-            const float bv = kk == 0 ? bf[slot][b].x : kk == 1 ? bf[slot][b].y : kk == 2 ? bf[slot][b].z : bf[slot][b].w;
-            acc[a][b] = MM::run(av, bv, acc[a][b]);
-          }
+        for (int i = 0; i < NM; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // one MFMA
+          if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // + a fragment read
+          if (first) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);           // + address VALU
+          if ((NKS == 2 || ks == 1) && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          if (last && NKS > 2 && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+          if (!first) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+        }
       }
     }
-    if (more) lstore(cur ^ 1);
     __syncthreads();
+    lfrag(par ^ 1, 0, 0);
+    mma((NKS - 1) & 1);
+    if constexpr (SCHED) {
+#pragma unroll
+      for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+      }
+    }
+  };
+
+  gload(0, 0);
+  lstore(0, 0);
+  gload(1, 1);
+  __syncthreads();
+  lfrag(0, 0, 0);
+  for (int kb = 0; kb < nkb; kb += 2) {
+    step(kb, std::integral_constant<int, 0>{});
+    if (kb + 1 < nkb) step(kb + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue: bias, identity shortcut, ReLU, mask; consecutive lanes store consecutive n ----
@@ -230,7 +286,11 @@ __global__ __launch_bounds__(NTHREADS) void igemm_fwd_fast_kernel(FwdProblem p, 
 template <int BM, int BN, int WM, int WN, int MF>
 hipError_t launch_cfg(const FwdProblem &p, const FastAux &q, hipStream_t st) {
   const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-  hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, WM, WN, MF>), dim3(tiles), dim3(NTHREADS), 0, st, p, q);
+  constexpr bool SCHED = MF == 32;
+  if (q.nkb_proj)
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, WM, WN, MF, true, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
+  else
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, WM, WN, MF, false, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
   return hipGetLastError();
 }
 
