@@ -24,8 +24,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 32;
-constexpr int LDK = BK + 4;
 constexpr int OOB = (int)0x80000000;      // offset no buffer of < 2 GiB contains
 constexpr int RSRC_FLAGS = 0x00020000;    // raw buffer, 32-bit data format
 
@@ -58,12 +56,16 @@ struct Mfma<16> {
   static __device__ inline int row(int e, int g) { return 4 * g + e; }  // g = lane / 16
 };
 
-template <int BM, int BN, int WM, int WN, int MF, bool PROJ, bool SCHED>
+// BK = reduction length staged per step (one barrier per step): 32 for the wide tiles, longer for
+// the skinny ones, whose steps are dominated by the fixed cost of the barrier.
+template <int BM, int BN, int BK, int WM, int WN, int MF, bool PROJ, bool SCHED>
 __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem p, FastAux q) {
   using MM = Mfma<MF>;
   using acc_t = typename MM::acc_t;
+  constexpr int LDK = BK + 4;        // +4 floats: 16-byte row reads of consecutive rows hit distinct banks
   constexpr int NTHREADS = WM * WN * 64;
-  constexpr int RPP = NTHREADS / 8;  // rows staged per pass (8 threads cover one row of BK floats)
+  constexpr int CPR = BK / 4;        // 16-byte chunks per staged row
+  constexpr int RPP = NTHREADS / CPR;  // rows staged per pass
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MT = TM / MF, NT = TN / MF;
   constexpr int PA = BM / RPP, PB = (BN + RPP - 1) / RPP;
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   const __amdgpu_buffer_rsrc_t rwp = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, q.wp_bytes, RSRC_FLAGS);
 
   // ---- per-thread gather state: chunk `ch` (4 consecutive kg) of rows row0 + RPP*i ----
-  const int ch = t & 7, row0 = t >> 3;
+  const int ch = t % CPR, row0 = t / CPR;
   int abase[PA], sbase[PA];
   uint32_t amask[PA];
 #pragma unroll
@@ -283,14 +285,16 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   }
 }
 
-template <int BM, int BN, int WM, int WN, int MF>
-hipError_t launch_cfg(const FwdProblem &p, const FastAux &q, hipStream_t st) {
+template <int BM, int BN, int BK, int WM, int WN, int MF>
+hipError_t launch_cfg(const FwdProblem &p, FastAux q, hipStream_t st) {
   const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   constexpr bool SCHED = MF == 32;
+  q.nkb_conv = (p.RSC + BK - 1) / BK;
+  q.nkb_proj = p.Cs ? (p.Cs + BK - 1) / BK : 0;
   if (q.nkb_proj)
-    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, WM, WN, MF, true, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, true, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
   else
-    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, WM, WN, MF, false, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, false, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
   return hipGetLastError();
 }
 
@@ -313,22 +317,21 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
   q.w_bytes = (uint32_t)((long long)p.N * p.RSC * 4);
   q.xs_bytes = p.Cs ? (uint32_t)(B * p.Hs * p.Ws * p.Cs * 4) : 0;
   q.wp_bytes = p.Cs ? (uint32_t)((long long)p.N * p.Cs * 4) : 0;
-  q.nkb_conv = (p.RSC + BK - 1) / BK;
-  q.nkb_proj = p.Cs ? (p.Cs + BK - 1) / BK : 0;
+  q.nkb_conv = q.nkb_proj = 0;  // set per tile configuration
   if (p.N > 64) {
     *kernel = "igemm_fwd_fast_128x128";
-    return launch_cfg<128, 128, 2, 2, 32>(p, q, st);
+    return launch_cfg<128, 128, 32, 2, 2, 32>(p, q, st);
   }
   if (p.N > 32) {
     *kernel = "igemm_fwd_fast_128x64";
-    return launch_cfg<128, 64, 2, 2, 32>(p, q, st);
+    return launch_cfg<128, 64, 32, 2, 2, 32>(p, q, st);
   }
   if (p.N > 16) {
     *kernel = "igemm_fwd_fast_128x32";
-    return launch_cfg<128, 32, 4, 1, 32>(p, q, st);
+    return launch_cfg<128, 32, 32, 4, 1, 32>(p, q, st);
   }
   *kernel = "igemm_fwd_fast_64x16";
-  return launch_cfg<64, 16, 4, 1, 16>(p, q, st);
+  return launch_cfg<64, 16, 128, 4, 1, 16>(p, q, st);
 }
 
 }  // namespace nf
