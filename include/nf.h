@@ -99,6 +99,17 @@ int32_t nf_layer_out_dims(const nf_layer_desc *d, int32_t *Ho, int32_t *Wo, int3
  * when only nf_layer_fwd will be called. */
 int32_t nf_workspace_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, size_t *out);
 
+/* Where two intermediates of the step live inside the workspace (byte offset and size), for
+ * callers that want to inspect them after nf_aux_fwd_loss / nf_local_step (tests compare the
+ * ReLU and max-pool decisions the kernels took):
+ *   NF_WS_AUX_ACT   the head's convolution output after its ReLU (Eq. 2, beta_n), fp32
+ *                   [B][Hu][Wu][A];
+ *   NF_WS_POOL_ARG  one byte per emitted element [B][Hp][Wp][C_out]: index u*pool_k+v of the
+ *                   window cell the max-pool P_n of Eq. 1 selected (size 0 when un-pooled). */
+enum { NF_WS_AUX_ACT = 0, NF_WS_POOL_ARG = 1 };
+int32_t nf_workspace_region(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, int32_t which,
+                            size_t *offset, size_t *bytes);
+
 /* Eq. 1.  x [B,H_in,W_in,C_in], x_skip per skip_kind (NULL if 0), y OUT [B,Hp,Wp,C_out].
  * Records in ws what the backward needs (pool arg-max). */
 int32_t nf_layer_fwd(const nf_layer_desc *d, int32_t B, const float *x, const float *x_skip,

@@ -128,6 +128,7 @@ class AuxFwd:
     z: np.ndarray
     loss: float
     dz: np.ndarray
+    Upre: np.ndarray | None = None
 
 
 def aux_fwd_loss(a: AuxDesc, y, labels, Wa, ba, Wf, bf) -> AuxFwd:
@@ -139,16 +140,21 @@ def aux_fwd_loss(a: AuxDesc, y, labels, Wa, ba, Wf, bf) -> AuxFwd:
     Pq = np.empty((B, a.A * a.pool_oh * a.pool_ow), dt)
     z = np.empty((B, a.n_classes), dt)
     dz = np.empty((B, a.n_classes), dt)
+    Upre = np.empty_like(U)
     loss = C.c_double()
     labels = np.ascontiguousarray(labels, np.int32)
     getattr(lib(), "nfo_aux_fwd_loss_" + _suf(dt))(
         C.byref(a), C.c_int32(B), _p(y), _p(labels), _p(Wa), _p(ba), _p(Wf), _p(bf),
-        _p(U), _p(Pq), _p(z), C.byref(loss), _p(dz))
-    return AuxFwd(U, Pq, z, float(loss.value), dz)
+        _p(U), _p(Pq), _p(z), C.byref(loss), _p(dz), _p(Upre))
+    return AuxFwd(U, Pq, z, float(loss.value), dz, Upre)
 
 
-def local_bwd(d: LayerDesc, a: AuxDesc, x, x_skip, lf: LayerFwd, af: AuxFwd, Wa, Wf):
-    """Gradients of the local loss w.r.t. the layer's and the head's parameters only."""
+def local_bwd(d: LayerDesc, a: AuxDesc, x, x_skip, lf: LayerFwd, af: AuxFwd, Wa, Wf, mask_u=None, mask_z=None):
+    """Gradients of the local loss w.r.t. the layer's and the head's parameters only.
+
+    mask_u / mask_z (uint8, shapes of U / Z) optionally replace the ReLU decisions U>0 / Z>0."""
+    mask_u = None if mask_u is None else np.ascontiguousarray(mask_u, np.uint8)
+    mask_z = None if mask_z is None else np.ascontiguousarray(mask_z, np.uint8)
     dt = x.dtype
     B = x.shape[0]
     F = a.A * a.pool_oh * a.pool_ow
@@ -167,7 +173,7 @@ def local_bwd(d: LayerDesc, a: AuxDesc, x, x_skip, lf: LayerFwd, af: AuxFwd, Wa,
         C.byref(d), C.byref(a), C.c_int32(B), _p(x), _p(x_skip), _p(lf.Z), _p(lf.Y), _p(lf.arg),
         _p(af.U), _p(af.Pq), _p(af.dz), _p(Wa), _p(Wf),
         _p(g["W"]), _p(g["b"]), _p(g["Wp"]), _p(g["Wa"]), _p(g["ba"]), _p(g["Wf"]), _p(g["bf"]),
-        _p(g["dY"]), _p(g["dZ"]))
+        _p(g["dY"]), _p(g["dZ"]), _p(mask_u), _p(mask_z))
     return g
 
 

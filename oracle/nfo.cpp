@@ -121,7 +121,7 @@ inline void adaptive_window(int i, int L, int O, int &lo, int &hi) {
 // ---------------------------------------------------------------------------------------
 template <typename T>
 void aux_fwd_loss(const nfo_aux_desc &a, int B, const T *y, const int32_t *labels, const T *Wa,
-                  const T *ba, const T *Wf, const T *bf, T *U, T *Pq, T *z, double *loss, T *dz) {
+                  const T *ba, const T *Wf, const T *bf, T *U, T *Pq, T *z, double *loss, T *dz, T *Upre) {
   const int K = a.C_in, H = a.H_in, Wd = a.W_in, A = a.A, R = a.R, S = a.S, p = a.pad;
   const int oh = a.pool_oh, ow = a.pool_ow, Cls = a.n_classes, F = A * oh * ow;
   // beta_n: stride-1 convolution, output has the input's spatial size when 2*pad = R-1
@@ -140,6 +140,7 @@ void aux_fwd_loss(const nfo_aux_desc &a, int B, const T *y, const int32_t *label
                 acc += (double)Wa[((int64_t)(q * K + k) * R + r) * S + s] *
                        (double)y[((int64_t)(n * K + k) * H + h) * Wd + w];
               }
+          if (Upre) Upre[((int64_t)(n * A + q) * Hu + i) * Wu + j] = (T)acc;  // before the ReLU
           if (a.relu && acc < 0.0) acc = 0.0;
           U[((int64_t)(n * A + q) * Hu + i) * Wu + j] = (T)acc;
         }
@@ -190,7 +191,11 @@ template <typename T>
 void local_bwd(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *x, const T *xs,
                const T *Z, const T *Y, const int32_t *arg, const T *U, const T *Pq, const T *dz,
                const T *Wa, const T *Wf, T *dW, T *db, T *dWp, T *dWa, T *dba, T *dWf, T *dbf,
-               T *dY_out, T *dZ_out) {
+               T *dY_out, T *dZ_out, const uint8_t *mask_u, const uint8_t *mask_z) {
+  // mask_u / mask_z (optional): the two ReLU decisions "U > 0" and "Z > 0" handed in by the
+  // caller instead of being taken here.  They exist for comparisons against an implementation
+  // that accumulates in another precision: where a pre-activation is zero to within rounding,
+  // both sides must differentiate the same branch of the ReLU.
   Dims o;
   if (!layer_dims(d, o)) return;
   const int C = d.C_in, H = d.H_in, Wd = d.W_in, K = d.C_out, R = d.R, S = d.S, st = d.stride,
@@ -237,7 +242,8 @@ void local_bwd(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *x
               acc += (double)dPq[(size_t)n * F + (q * oh + i) * ow + j] / (double)((h1 - h0) * (w1 - w0));
             }
           const int64_t e = ((int64_t)(n * A + q) * Hu + h) * Wu + w;
-          if (a.relu && !(U[e] > (T)0)) acc = 0.0;
+          const bool on = mask_u ? mask_u[e] != 0 : U[e] > (T)0;
+          if (a.relu && !on) acc = 0.0;
           dU[(size_t)e] = (T)acc;
         }
   // beta_n: weight and bias gradient
@@ -290,13 +296,18 @@ void local_bwd(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *x
     for (int k = 0; k < K; ++k) {
       const int64_t zb = (int64_t)(n * K + k) * Ho * Wo, yb = (int64_t)(n * K + k) * Hp * Wp_;
       if (d.pool_kind == 0) {
-        for (int e = 0; e < Ho * Wo; ++e) dZ[(size_t)(zb + e)] = Z[zb + e] > (T)0 ? dY[(size_t)(yb + e)] : (T)0;
+        for (int e = 0; e < Ho * Wo; ++e) {
+          const bool on = mask_z ? mask_z[zb + e] != 0 : Z[zb + e] > (T)0;
+          dZ[(size_t)(zb + e)] = on ? dY[(size_t)(yb + e)] : (T)0;
+        }
       } else {
         // overlapping windows may elect the same cell more than once: sum in double
         std::vector<double> plane((size_t)Ho * Wo, 0.0);
         for (int e = 0; e < Hp * Wp_; ++e) {
           const int32_t t = arg[yb + e];
-          if (t >= 0 && Z[zb + t] > (T)0) plane[(size_t)t] += (double)dY[(size_t)(yb + e)];
+          if (t < 0) continue;
+          const bool on = mask_z ? mask_z[zb + t] != 0 : Z[zb + t] > (T)0;
+          if (on) plane[(size_t)t] += (double)dY[(size_t)(yb + e)];
         }
         for (int e = 0; e < Ho * Wo; ++e) dZ[(size_t)(zb + e)] = (T)plane[(size_t)e];
       }
@@ -391,11 +402,11 @@ void local_step(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *
   std::vector<T> tW(nW), tb(K), tWp(nWp), tWa(nWa), tba(A), tWf(nWf), tbf(Cls);
   // lines 3-5 of Algorithm 2
   layer_fwd<T>(d, B, x, xs, W, b, Wp, Z.data(), Y, arg.empty() ? nullptr : arg.data());
-  aux_fwd_loss<T>(a, B, Y, labels, Wa, ba, Wf, bf, U.data(), Pq.data(), z.data(), loss, dz.data());
+  aux_fwd_loss<T>(a, B, Y, labels, Wa, ba, Wf, bf, U.data(), Pq.data(), z.data(), loss, dz.data(), nullptr);
   // line 6
   local_bwd<T>(d, a, B, x, xs, Z.data(), Y, arg.empty() ? nullptr : arg.data(), U.data(), Pq.data(),
                dz.data(), Wa, Wf, tW.data(), tb.data(), nWp ? tWp.data() : nullptr, tWa.data(), tba.data(),
-               tWf.data(), tbf.data(), nullptr, nullptr);
+               tWf.data(), tbf.data(), nullptr, nullptr, nullptr, nullptr);
   // line 7
   sgd_update<T>(nW, W, tW.data(), vW, lr, mu);
   sgd_update<T>(K, b, tb.data(), vb, lr, mu);
@@ -447,15 +458,16 @@ void nfo_set_num_threads(int32_t n) {
   }                                                                                                \
   void nfo_aux_fwd_loss_##SUF(const nfo_aux_desc *a, int32_t B, const T *y, const int32_t *labels, \
                               const T *Wa, const T *ba, const T *Wf, const T *bf, T *U, T *Pq,     \
-                              T *z, double *loss, T *dz) {                                         \
-    aux_fwd_loss<T>(*a, B, y, labels, Wa, ba, Wf, bf, U, Pq, z, loss, dz);                         \
+                              T *z, double *loss, T *dz, T *Upre) {                                \
+    aux_fwd_loss<T>(*a, B, y, labels, Wa, ba, Wf, bf, U, Pq, z, loss, dz, Upre);                   \
   }                                                                                                \
   void nfo_local_bwd_##SUF(const nfo_layer_desc *d, const nfo_aux_desc *a, int32_t B, const T *x,  \
                            const T *x_skip, const T *Z, const T *Y, const int32_t *arg,            \
                            const T *U, const T *Pq, const T *dz, const T *Wa, const T *Wf, T *dW,  \
-                           T *db, T *dWp, T *dWa, T *dba, T *dWf, T *dbf, T *dY, T *dZ) {          \
+                           T *db, T *dWp, T *dWa, T *dba, T *dWf, T *dbf, T *dY, T *dZ,            \
+                           const uint8_t *mask_u, const uint8_t *mask_z) {                         \
     local_bwd<T>(*d, *a, B, x, x_skip, Z, Y, arg, U, Pq, dz, Wa, Wf, dW, db, dWp, dWa, dba, dWf,   \
-                 dbf, dY, dZ);                                                                     \
+                 dbf, dY, dZ, mask_u, mask_z);                                                     \
   }                                                                                                \
   void nfo_sgd_update_##SUF(int64_t numel, T *w, const T *g, T *v, double lr, double mu) {         \
     sgd_update<T>(numel, w, g, v, lr, mu);                                                         \

@@ -63,18 +63,24 @@ void nfo_set_num_threads(int32_t n);
                            const T *W, const T *b, const T *Wp, T *Z, T *Y, int32_t *arg);     \
   /* Eq. 2 + Eq. 3 (cross-entropy, batch mean).  U[B,A,H,W] post-ReLU aux conv output,      */ \
   /* Pq[B,A*oh*ow] pooled features (flatten order a,i,j), z[B,Cls] logits, *loss the batch  */ \
-  /* mean, dz[B,Cls] = d loss / d z.                                                        */ \
+  /* mean, dz[B,Cls] = d loss / d z.  Upre (optional) receives the aux conv output before   */ \
+  /* its ReLU.                                                                              */ \
   void nfo_aux_fwd_loss_##SUF(const nfo_aux_desc *a, int32_t B, const T *y,                    \
                               const int32_t *labels, const T *Wa, const T *ba, const T *Wf,    \
-                              const T *bf, T *U, T *Pq, T *z, double *loss, T *dz);            \
+                              const T *bf, T *U, T *Pq, T *z, double *loss, T *dz, T *Upre);   \
   /* Algorithm 2, "compute the gradient w.r.t. (theta_n, beta_n, gamma_n)".  Consumes what  */ \
   /* the two forward calls produced.  dY/dZ are optional outputs (may be NULL).  No         */ \
   /* gradient is formed for x or x_skip.  dWp may be NULL unless skip_kind==2.              */ \
+  /* mask_u [B,A,Hu,Wu] / mask_z [B,K,Ho,Wo] (optional, 0/1 bytes) replace the decisions    */ \
+  /* "U > 0" / "Z > 0" of the two ReLU derivatives; `arg` is an input in any case.  They let */ \
+  /* a comparison hand over the branch taken by an implementation that accumulates in        */ \
+  /* another precision, for pre-activations that are zero to within rounding.                */ \
   void nfo_local_bwd_##SUF(const nfo_layer_desc *d, const nfo_aux_desc *a, int32_t B,          \
                            const T *x, const T *x_skip, const T *Z, const T *Y,                \
                            const int32_t *arg, const T *U, const T *Pq, const T *dz,           \
                            const T *Wa, const T *Wf, T *dW, T *db, T *dWp, T *dWa, T *dba,     \
-                           T *dWf, T *dbf, T *dY, T *dZ);                                      \
+                           T *dWf, T *dbf, T *dY, T *dZ, const uint8_t *mask_u,                \
+                           const uint8_t *mask_z);                                             \
   /* Algorithm 2, "update": v = mu*v + g ; w = w - lr*v.  v==NULL or mu==0: w = w - lr*g.   */ \
   void nfo_sgd_update_##SUF(int64_t numel, T *w, const T *g, T *v, double lr, double mu);      \
   /* Activation cache: row r of `cache` is one sample (sample_elems values).               */  \

@@ -19,7 +19,9 @@ NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE
 
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
-           "nf_prof_begin", "nf_prof_end")
+           "nf_prof_begin", "nf_prof_end", "nf_workspace_region")
+
+NF_WS_AUX_ACT, NF_WS_POOL_ARG = 0, 1
 
 
 class NfError(RuntimeError):
@@ -94,6 +96,8 @@ def lib():
                                     C.POINTER(AuxParams), C.POINTER(LayerParams), C.POINTER(AuxParams),
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nf_prof_end.argtypes = [C.POINTER(ProfRecord), C.c_int32, C.POINTER(C.c_int32)]
+        L.nf_workspace_region.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
+                                          C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         _lib = L
     return _lib
 
@@ -144,6 +148,14 @@ def nf_workspace_bytes(d: LayerDesc, a: AuxDesc | None, B: int) -> int:
     _check(lib().nf_workspace_bytes(C.byref(d), C.byref(a) if a is not None else None, B, C.byref(out)),
            "nf_workspace_bytes")
     return int(out.value)
+
+
+def nf_workspace_region(d: LayerDesc, a: AuxDesc | None, B: int, which: int):
+    """(byte offset, byte size) of an intermediate inside the workspace."""
+    off, nb = C.c_size_t(), C.c_size_t()
+    _check(lib().nf_workspace_region(C.byref(d), C.byref(a) if a is not None else None, B, which, C.byref(off),
+                                     C.byref(nb)), "nf_workspace_region")
+    return int(off.value), int(nb.value)
 
 
 def _ws(ws):

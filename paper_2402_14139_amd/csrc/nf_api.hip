@@ -432,6 +432,32 @@ int32_t nf_workspace_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t
   return NF_OK;
 }
 
+int32_t nf_workspace_region(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, int32_t which,
+                            size_t *offset, size_t *bytes) {
+  if (!offset || !bytes) return NF_ERR_NULL;
+  LayerDims ld;
+  AuxDims ad = {0, 0, 0};
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if (a) {
+    if ((rc = check_aux(a, &ad))) return rc;
+    if ((rc = check_pair(d, ld, a))) return rc;
+  }
+  const WsLayout w = ws_layout(d, ld, a, ad, B);
+  if (which == NF_WS_AUX_ACT) {
+    if (!a) return NF_ERR_NULL;
+    *offset = w.U;
+    *bytes = (size_t)B * ad.Hu * ad.Wu * a->A * sizeof(float);
+  } else if (which == NF_WS_POOL_ARG) {
+    *offset = w.arg;
+    *bytes = d->pool_kind ? (size_t)B * ld.Hp * ld.Wp * d->C_out : 0;
+  } else {
+    return NF_ERR_BAD_DESC;
+  }
+  return NF_OK;
+}
+
 int32_t nf_layer_fwd(const nf_layer_desc *d, int32_t B, const float *x, const float *x_skip,
                      const nf_layer_params *p, float *y, void *ws, size_t ws_bytes, void *stream) {
   LayerDims ld;

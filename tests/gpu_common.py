@@ -57,6 +57,76 @@ def gpu_layer(spec, n_classes, p, B, momentum, relu=1):
     return LocalLayer(d, a, layout.params_to_lib(p, spec.A), B, momentum)
 
 
+TIE = 2e-5  # a pre-activation within TIE * max|.| of zero (or of the window maximum) is a tie
+
+
+def gpu_decisions(L, spec, B, y_gpu):
+    """The discrete decisions the kernels took, in the oracle's index convention:
+    aux ReLU mask [B,A,Hu,Wu], emitted activation [B,K,Hp,Wp], pool arg-max as flat h*Wo+w."""
+    ws = L.ws
+    off, nb = nf.nf_workspace_region(L.d, L.a, B, nf.NF_WS_AUX_ACT)
+    U = ws[off:off + nb].view(torch.float32).view(B, spec.Hp, spec.Wp, spec.A).cpu().numpy()
+    mask_u = layout.act_from_lib(U) > 0
+    arg = None
+    if spec.pool_kind:
+        off, nb = nf.nf_workspace_region(L.d, L.a, B, nf.NF_WS_POOL_ARG)
+        loc = ws[off:off + nb].view(B, spec.Hp, spec.Wp, spec.C_out).cpu().numpy().astype(np.int64)
+        loc = np.ascontiguousarray(loc.transpose(0, 3, 1, 2))
+        u, v = loc // spec.pool_k, loc % spec.pool_k
+        ii = np.arange(spec.Hp)[None, None, :, None] * spec.pool_stride - spec.pool_pad
+        jj = np.arange(spec.Wp)[None, None, None, :] * spec.pool_stride - spec.pool_pad
+        hh, ww = ii + u, jj + v
+        assert hh.min() >= 0 and hh.max() < spec.Ho and ww.min() >= 0 and ww.max() < spec.Wo, "arg-max outside the map"
+        arg = (hh * spec.Wo + ww).astype(np.int32)
+    return mask_u, layout.act_from_lib(y_gpu), arg
+
+
+def oracle_step(od, oa, spec, x, xs, labels, po, mo, lr, mu, dec):
+    """One local step of the oracle (forward, head, loss, gradients, update in place), taking the
+    ReLU / max-pool decisions from `dec` (the kernels') wherever the oracle's own pre-activation
+    is a tie; anywhere else the two must agree, which is asserted."""
+    mask_u_gpu, y_gpu, arg_gpu = dec
+    lf = O.layer_fwd(od, x, xs, po["W"], po["b"], po["Wp"])
+    af = O.aux_fwd_loss(oa, lf.Y, labels, po["Wa"], po["ba"], po["Wf"], po["bf"])
+    tol_z = TIE * np.abs(lf.Z).max()
+    mask_z = lf.Z > 0
+    arg = lf.arg
+    n_tie = 0
+    if not spec.pool_kind:
+        g_on = y_gpu > 0
+        diff = g_on != mask_z
+        assert np.all(np.abs(lf.Z[diff]) <= tol_z), "layer ReLU decision differs away from a tie"
+        n_tie += int(diff.sum())
+        mask_z = g_on
+    else:
+        flatZ = lf.Z.reshape(lf.Z.shape[0], lf.Z.shape[1], -1)
+        picked = np.take_along_axis(flatZ, arg_gpu.reshape(*arg_gpu.shape[:2], -1).astype(np.int64), axis=2)
+        picked = np.maximum(picked.reshape(lf.Y.shape), 0)
+        assert np.all(picked >= lf.Y - tol_z), "max-pool selection differs away from a tie"
+        n_tie += int((arg_gpu != lf.arg).sum())
+        arg = arg_gpu
+        on = y_gpu > 0  # per pooled cell: the kernel's decision for the cell it selected
+        sel = np.take_along_axis(flatZ, arg.reshape(*arg.shape[:2], -1).astype(np.int64), axis=2).reshape(lf.Y.shape)
+        diff = on != (sel > 0)
+        assert np.all(np.abs(sel[diff]) <= tol_z), "layer ReLU decision differs away from a tie"
+        n_tie += int(diff.sum())
+        mz = mask_z.reshape(flatZ.shape).copy()
+        np.put_along_axis(mz, arg.reshape(*arg.shape[:2], -1).astype(np.int64), on.reshape(*on.shape[:2], -1), axis=2)
+        mask_z = mz.reshape(lf.Z.shape)
+    mask_u = af.Upre > 0
+    if oa.relu:
+        diff = mask_u_gpu != mask_u
+        assert np.all(np.abs(af.Upre[diff]) <= TIE * np.abs(af.Upre).max()), "aux ReLU decision differs away from a tie"
+        n_tie += int(diff.sum())
+        mask_u = mask_u_gpu
+    lf = O.LayerFwd(lf.Z, lf.Y, arg)
+    g = O.local_bwd(od, oa, x, xs, lf, af, po["Wa"], po["Wf"], mask_u=mask_u, mask_z=mask_z)
+    for k in PARAM_NAMES:
+        if po[k] is not None:
+            O.sgd_update(po[k], g[k], None if mo is None else mo[k], lr, mu)
+    return lf.Y, af.loss, g, n_tie
+
+
 def run_step_both(spec, n_classes, B, seed, lr, mu, steps=1, relu=1, bias_std=0.1):
     """Runs `steps` local steps on the same batch through the library and the oracle; returns
     per-step (loss, grads, y) for both and the final params/momentum for both."""
@@ -72,8 +142,12 @@ def run_step_both(spec, n_classes, B, seed, lr, mu, steps=1, relu=1, bias_std=0.
         torch.cuda.synchronize()
         g_loss = float(L.loss.item())
         g_grads = L.params_numpy("g")
-        g_y = layout.act_from_lib(y.cpu().numpy())
-        oY, oloss, ograds = O.local_step(od, oa, x, xs, labels, po, mo, lr, mu)
+        y_np = y.cpu().numpy()
+        g_y = layout.act_from_lib(y_np)
+        oY, oloss, ograds, n_tie = oracle_step(od, oa, spec, x, xs, labels, po, mo, lr, mu,
+                                               gpu_decisions(L, spec, B, y_np))
+        if n_tie:
+            print(f"  {n_tie} tie decision(s) taken from the kernels", flush=True)
         out.append(((g_loss, g_grads, g_y), (oloss, ograds, oY)))
     final = (L.params_numpy("p"), L.params_numpy("v") if mu != 0 else None), (po, mo)
     return out, final

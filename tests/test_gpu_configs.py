@@ -1,0 +1,44 @@
+"""GPU parity on the benchmark configurations' own layer shapes.
+
+* the ResNet-18-style configuration at FULL block batch sizes (64/128/256/512), i.e. in the
+  launch configuration bench.py times: one layer of each kind (stem, identity shortcut,
+  projection shortcut, stride-2, widest), whole local step against the oracle;
+* every layer of the VGG-11-style configuration and sampled layers of the VGG-16- and
+  ResNet-34-style ones at a reduced batch (the oracle is a plain loop nest).
+"""
+import pytest
+
+import workloads
+from tests import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(cfg_name, li, B, steps=1):
+    cfg = workloads.config(cfg_name)
+    spec = cfg.layers[li]
+    print(f"{cfg_name} layer {li} ({spec.name}) B={B}", flush=True)
+    out, final = G.run_step_both(spec, cfg.n_classes, B, seed=cfg.seed * 100 + li, lr=cfg.lr, mu=cfg.momentum,
+                                 steps=steps, bias_std=0.05)
+    G.check_step_results(f"{cfg_name}[{li}]", out, final)
+
+
+@pytest.mark.parametrize("li", [0, 2, 6, 9, 13, 16])
+def test_cfg3_full_batch(li):
+    cfg = workloads.config("cfg3")
+    _run("cfg3", li, cfg.blocks[cfg.layers[li].block].batch)
+
+
+@pytest.mark.parametrize("li", list(range(8)))
+def test_cfg2_all_layers_small_batch(li):
+    _run("cfg2", li, 8, steps=2)
+
+
+@pytest.mark.parametrize("li", [0, 1, 3, 6, 9, 12])
+def test_cfg4_sampled_layers_small_batch(li):
+    _run("cfg4", li, 2)
+
+
+@pytest.mark.parametrize("li", [0, 1, 8, 16, 32])
+def test_cfg5_sampled_layers_small_batch(li):
+    _run("cfg5", li, 2)

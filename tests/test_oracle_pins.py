@@ -422,3 +422,22 @@ def test_f32_matches_f64(oracle):
     for k in g64:
         if g64[k] is not None:
             np.testing.assert_allclose(g32[k], g64[k], rtol=2e-5, atol=1e-6)
+
+
+# ---- decision overrides: handing the oracle its own decisions changes nothing; flipping one
+# ---- decision changes the gradient by exactly that element's contribution
+def test_decision_overrides(oracle):
+    o = oracle
+    ls = _spec(H=6, W=6, pool=(2, 2, 0))
+    d, a, x, xs, labels, p = _setup(o, ls, B=3, Cls=4)
+    lf, af, g = _grads(o, d, a, x, xs, labels, p)
+    g2 = o.local_bwd(d, a, x, xs, lf, af, p["Wa"], p["Wf"], mask_u=af.Upre > 0, mask_z=lf.Z > 0)
+    for k in g:
+        if g[k] is not None:
+            assert np.array_equal(g[k], g2[k]), k
+    assert np.array_equal(np.maximum(af.Upre, 0), af.U)
+    mu = (af.Upre > 0).copy()
+    on = np.argwhere(mu)[0]
+    mu[tuple(on)] = False  # switch one active aux unit off
+    g3 = o.local_bwd(d, a, x, xs, lf, af, p["Wa"], p["Wf"], mask_u=mu, mask_z=lf.Z > 0)
+    assert not np.array_equal(g3["Wa"], g["Wa"]) and np.array_equal(g3["Wf"], g["Wf"])
