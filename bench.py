@@ -247,29 +247,43 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as O
-        blk = cfg.blocks[0]
-        B = blk.batch
-        xb, yb = workloads.gen_batch(cfg.seed, 0, B, cfg.in_shape, cls)
-        specs = [cfg.layers[li] for li in blk.layers]
-        params = [workloads.gen_layer_params(cfg.seed, li, cfg.layers[li], cls) for li in blk.layers]
-        moms = [{k: (None if v is None else np.zeros_like(v)) for k, v in p.items()} for p in params]
-        t0 = time.perf_counter()
-        cur, outs = xb, {}
-        for i, (li, ls) in enumerate(zip(blk.layers, specs)):
-            xs = None
-            if ls.skip_kind:
-                xs = xb if ls.skip_src == blk.layers[0] else outs[ls.skip_src - 1]
-            od, oa = O.layer_desc(**ls.layer_desc_fields()), O.aux_desc(**ls.aux_desc_fields(cls))
-            Y, _, _ = O.local_step(od, oa, cur, xs, yb, params[i], moms[i], cfg.lr, cfg.momentum)
-            outs[li] = Y
-            cur = Y
-        t_cpu = time.perf_counter() - t0
-        fl_sample = sum(layer_flops(ls, B, cls) for ls in specs)
+        # One local step of each layer at its block's batch size, in network order, until about
+        # 25 s of CPU time have been spent (the whole step if it fits); scaled by FLOPs to the
+        # full step.  Block inputs are synthetic post-ReLU tensors of the right shape.
+        budget_s, t_cpu, fl_sample, done = 25.0, 0.0, 0.0, []
+        gcpu = workloads.rng_for(cfg.seed, "cpu-baseline")
+        for k, blk in enumerate(cfg.blocks):
+            if t_cpu >= budget_s:
+                break
+            B = blk.batch
+            f = cfg.layers[blk.layers[0]]
+            xb = gcpu.standard_normal((B, f.C_in, f.H_in, f.W_in)).astype(np.float32)
+            if k > 0:
+                xb = np.maximum(xb, 0)
+            yb = gcpu.integers(0, cls, size=(B,)).astype(np.int32)
+            cur, outs = xb, {}
+            for li in blk.layers:
+                if t_cpu >= budget_s:
+                    break
+                ls = cfg.layers[li]
+                pr = workloads.gen_layer_params(cfg.seed, li, ls, cls)
+                mo = {kk: (None if v is None else np.zeros_like(v)) for kk, v in pr.items()}
+                xs = None
+                if ls.skip_kind:
+                    xs = xb if ls.skip_src == blk.layers[0] else outs[ls.skip_src - 1]
+                od, oa = O.layer_desc(**ls.layer_desc_fields()), O.aux_desc(**ls.aux_desc_fields(cls))
+                t0 = time.perf_counter()
+                Y, _, _ = O.local_step(od, oa, cur, xs, yb, pr, mo, cfg.lr, cfg.momentum)
+                t_cpu += time.perf_counter() - t0
+                fl_sample += layer_flops(ls, B, cls)
+                outs[li] = Y
+                cur = Y
+                done.append(li)
         scaled_step_s = t_cpu * flops_per_step / fl_sample
         cpu = {"value": round(images_per_step / scaled_step_s, 3), "unit": "images/s", "cores": O.num_threads(),
                "kind": "oracle",
-               "sample": f"block 1 of {cfg.name} (its {len(specs)} layers, one local step each at B={B}: "
-                         f"{fl_sample / 1e9:.1f} of the step's {flops_per_step / 1e9:.1f} GFLOP) took {t_cpu:.2f} s; "
+               "sample": f"one local step of layers {done[0]}..{done[-1]} of {cfg.name} at their block batch sizes "
+                         f"({fl_sample / 1e9:.1f} of the step's {flops_per_step / 1e9:.1f} GFLOP) took {t_cpu:.2f} s; "
                          f"scaled by FLOPs to the full step",
                "gflops": round(fl_sample / t_cpu / 1e9, 2)}
         log(f"[cpu] oracle {t_cpu:.2f}s on {O.num_threads()} threads, {fl_sample / t_cpu / 1e9:.2f} GFLOP/s")

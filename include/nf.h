@@ -55,8 +55,8 @@ typedef enum {
 } nf_status;
 
 /* Layer n of Eq. 1: conv theta_n (+bias, + optional shortcut), ReLU, optional max-pool P_n.
- * Supported: R,S in {1,3,5,7}, stride in {1,2}, pad <= R/2 ... any pad < R; max-pool with
- * 2*pool_pad <= pool_k <= 3, pool_stride in {1,2,3}. */
+ * Supported: 1 <= R,S <= 15, 1 <= stride <= 4, any pad >= 0 that leaves an output; max-pool with
+ * 2*pool_pad <= pool_k <= 15 and any positive stride.  Anything else: NF_ERR_UNSUPPORTED. */
 typedef struct {
   int32_t C_in, H_in, W_in;
   int32_t C_out, R, S, stride, pad;
