@@ -26,61 +26,86 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
-// One workgroup per sample: pool U[n] -> Pq[n], logits, log-sum-exp, per-sample loss, dL/dz.
-// Dynamic LDS: Pq (F floats) + z (Cls floats) + partial pool sums (G*F floats) + 8 scratch.
-__global__ __launch_bounds__(HT) void head_fwd_kernel(HeadShape s, const float *__restrict__ U,
-                                                      const int32_t *__restrict__ labels,
-                                                      const float *__restrict__ Wf, const float *__restrict__ bf,
-                                                      float *__restrict__ Pq, float *__restrict__ dz,
-                                                      float *__restrict__ loss_n, int G) {
-  extern __shared__ float sm[];
-  float *pq = sm;               // [F]
-  float *z = pq + s.F;          // [Cls]
-  float *part = z + s.Cls;      // [G][F]
-  float *red = part + G * s.F;  // [8]
-  const int n = blockIdx.x, t = threadIdx.x;
+// F_n: adaptive average pool.  One workgroup per (sample, output cell); its threads are
+// CA channel groups (V channels each, 16-byte loads when V == 4) x NS window-position slices;
+// slice sums are added in order through LDS.
+template <int V>
+__global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, const float *__restrict__ U,
+                                                       float *__restrict__ Pq) {
+  __shared__ float red[HT * V];
+  const int t = threadIdx.x;
+  const int n = blockIdx.x / (s.oh * s.ow), cell = blockIdx.x % (s.oh * s.ow);
+  const int ci = cell / s.ow, cj = cell - ci * s.ow;
+  int h0, h1, w0, w1;
+  adaptive_window(ci, s.Hu, s.oh, h0, h1);
+  adaptive_window(cj, s.Wu, s.ow, w0, w1);
+  const int ww = w1 - w0, npos = (h1 - h0) * ww;
+  const int AV = s.A / V;
+  const int CA = AV < HT ? AV : HT, NS = HT / CA;
+  const int lane = t % CA, slice = t / CA;
+  const float inv = 1.f / (float)npos;
   const float *Un = U + (long long)n * s.Hu * s.Wu * s.A;
-
-  // ---- F_n: adaptive average pool; group g of G sums every G-th row of each window ----
-  for (int idx = t; idx < G * s.F; idx += HT) {
-    const int g = idx / s.F, f = idx - g * s.F;
-    const int cell = f / s.A, a = f - cell * s.A;
-    const int i = cell / s.ow, jj = cell - i * s.ow;
-    int h0, h1, w0, w1;
-    adaptive_window(i, s.Hu, s.oh, h0, h1);
-    adaptive_window(jj, s.Wu, s.ow, w0, w1);
-    float acc = 0.f;
-    for (int hh = h0 + g; hh < h1; hh += G)
-      for (int ww = w0; ww < w1; ++ww) acc += Un[((long long)hh * s.Wu + ww) * s.A + a];
-    part[idx] = acc;
+  for (int c0 = 0; c0 < AV; c0 += CA) {
+    const int col = c0 + lane;
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    if (col < AV && slice < NS) {
+      for (int pos = slice; pos < npos; pos += NS) {
+        const int hh = h0 + pos / ww, wx = w0 + pos % ww;
+        const float *src = Un + ((long long)hh * s.Wu + wx) * s.A + col * V;
+        if constexpr (V == 4) {
+          const float4 v = *reinterpret_cast<const float4 *>(src);
+          acc[0] += v.x, acc[1] += v.y, acc[2] += v.z, acc[3] += v.w;
+        } else {
+          acc[0] += src[0];
+        }
+      }
+    }
+    __syncthreads();  // previous round's reads of red are done
+#pragma unroll
+    for (int e = 0; e < V; ++e) red[t * V + e] = acc[e];
+    __syncthreads();
+    if (slice == 0 && col < AV) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        float sum = acc[e];
+        for (int k = 1; k < NS; ++k) sum += red[(k * CA + lane) * V + e];
+        Pq[(long long)n * s.F + cell * s.A + col * V + e] = sum * inv;
+      }
+    }
   }
-  __syncthreads();
-  for (int f = t; f < s.F; f += HT) {
-    const int cell = f / s.A;
-    const int i = cell / s.ow, jj = cell - i * s.ow;
-    int h0, h1, w0, w1;
-    adaptive_window(i, s.Hu, s.oh, h0, h1);
-    adaptive_window(jj, s.Wu, s.ow, w0, w1);
-    float acc = 0.f;
-    for (int g = 0; g < G; ++g) acc += part[g * s.F + f];
-    const float v = acc / (float)((h1 - h0) * (w1 - w0));
-    pq[f] = v;
-    Pq[(long long)n * s.F + f] = v;
-  }
-  __syncthreads();
+}
 
-  // ---- gamma_n: one wavefront per class, lanes over features ----
-  const int lane = t & 63, wave = t >> 6;
-  for (int q = wave; q < s.Cls; q += HT / 64) {
+// gamma_n and Eq. 3 for one sample per workgroup: logits (one thread per class, the pooled
+// features staged in LDS), log-sum-exp, per-sample loss, dL/dz.  Dynamic LDS: F + Cls + 8 floats.
+__global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *__restrict__ Pq,
+                                                     const int32_t *__restrict__ labels,
+                                                     const float *__restrict__ Wf, const float *__restrict__ bf,
+                                                     float *__restrict__ dz, float *__restrict__ loss_n) {
+  extern __shared__ float sm[];
+  float *pq = sm;           // [F]
+  float *z = pq + s.F;      // [Cls]
+  float *red = z + s.Cls;   // [8]
+  const int n = blockIdx.x, t = threadIdx.x;
+  for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
+  __syncthreads();
+  for (int q = t; q < s.Cls; q += HT) {
     const float *wr = Wf + (long long)q * s.F;
     float acc = 0.f;
-    for (int f = lane; f < s.F; f += 64) acc += wr[f] * pq[f];
-    acc = wave_sum(acc);
-    if (lane == 0) z[q] = acc + (bf ? bf[q] : 0.f);
+    if ((s.F & 3) == 0) {
+      for (int f = 0; f < s.F; f += 4) {
+        const float4 w = *reinterpret_cast<const float4 *>(wr + f);
+        acc += w.x * pq[f] + w.y * pq[f + 1] + w.z * pq[f + 2] + w.w * pq[f + 3];
+      }
+    } else {
+      for (int f = 0; f < s.F; ++f) acc += wr[f] * pq[f];
+    }
+    z[q] = acc + (bf ? bf[q] : 0.f);
   }
   __syncthreads();
 
-  // ---- softmax cross-entropy ----
+  const int lane = t & 63, wave = t >> 6;
   float m = -INFINITY;
   for (int q = t; q < s.Cls; q += HT) m = fmaxf(m, z[q]);
   m = wave_max(m);
@@ -161,44 +186,86 @@ __global__ __launch_bounds__(HT) void fc_bwd_kernel(HeadShape s, const float *__
   }
 }
 
-// F_n backward + the aux ReLU mask: dU = [U > 0] * sum over windows containing (h,w) of dPq / |window|
+// F_n backward + the aux ReLU mask: dU = [U > 0] * sum over windows containing (h,w) of dPq / |window|,
+// V channels per thread.  Workgroups past `nb_main` re-lay the aux filter for the data gradient:
+// WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] (same launch: one kernel less per step).
+template <int V>
 __global__ __launch_bounds__(HT) void pool_relu_bwd_kernel(HeadShape s, const float *__restrict__ U,
-                                                           const float *__restrict__ dPq, float *__restrict__ dU) {
-  const long long total = (long long)s.B * s.Hu * s.Wu * s.A;
+                                                           const float *__restrict__ dPq, float *__restrict__ dU,
+                                                           int nb_main, const float *__restrict__ Wa,
+                                                           float *__restrict__ WaT, int R, int S, int K) {
+  if ((int)blockIdx.x >= nb_main) {
+    const long long total = (long long)s.A * R * S * K;
+    const long long i = (long long)(blockIdx.x - nb_main) * HT + threadIdx.x;
+    if (i >= total) return;
+    const int a = (int)(i % s.A);
+    long long r = i / s.A;
+    const int sx = (int)(r % S);
+    r /= S;
+    const int rr = (int)(r % R);
+    const int k = (int)(r / R);
+    WaT[i] = Wa[(((long long)a * R + (R - 1 - rr)) * S + (S - 1 - sx)) * K + k];
+    return;
+  }
+  const int AV = s.A / V;
+  const long long total = (long long)s.B * s.Hu * s.Wu * AV;
   const long long i = (long long)blockIdx.x * HT + threadIdx.x;
   if (i >= total) return;
-  const int a = (int)(i % s.A);
-  long long r = i / s.A;
+  const int av = (int)(i % AV);
+  long long r = i / AV;
   const int w = (int)(r % s.Wu);
   r /= s.Wu;
   const int hh = (int)(r % s.Hu);
   const int n = (int)(r / s.Hu);
-  float acc = 0.f;
-  if (!s.relu || U[i] > 0.f) {
-    for (int ci = 0; ci < s.oh; ++ci) {
-      int h0, h1;
-      adaptive_window(ci, s.Hu, s.oh, h0, h1);
-      if (hh < h0 || hh >= h1) continue;
-      for (int cj = 0; cj < s.ow; ++cj) {
-        int w0, w1;
-        adaptive_window(cj, s.Wu, s.ow, w0, w1);
-        if (w < w0 || w >= w1) continue;
-        acc += dPq[(long long)n * s.F + (ci * s.ow + cj) * s.A + a] / (float)((h1 - h0) * (w1 - w0));
-      }
+  const long long e0 = i * V;
+  float u[V], acc[V];
+  if constexpr (V == 4) {
+    const float4 t4 = *reinterpret_cast<const float4 *>(U + e0);
+    u[0] = t4.x, u[1] = t4.y, u[2] = t4.z, u[3] = t4.w;
+  } else {
+    u[0] = U[e0];
+  }
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  for (int ci = 0; ci < s.oh; ++ci) {
+    int h0, h1;
+    adaptive_window(ci, s.Hu, s.oh, h0, h1);
+    if (hh < h0 || hh >= h1) continue;
+    for (int cj = 0; cj < s.ow; ++cj) {
+      int w0, w1;
+      adaptive_window(cj, s.Wu, s.ow, w0, w1);
+      if (w < w0 || w >= w1) continue;
+      const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
+      const float *src = dPq + (long long)n * s.F + (ci * s.ow + cj) * s.A + av * V;
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
     }
   }
-  dU[i] = acc;
+#pragma unroll
+  for (int e = 0; e < V; ++e)
+    if (s.relu && !(u[e] > 0.f)) acc[e] = 0.f;
+  if constexpr (V == 4) {
+    *reinterpret_cast<float4 *>(dU + e0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  } else {
+    dU[e0] = acc[0];
+  }
 }
 
 }  // namespace
 
-hipError_t launch_head_fwd(const HeadShape &h, const float *U, const int32_t *labels, const float *Wf,
-                           const float *bf, float *Pq, float *dz, float *loss_n, hipStream_t st) {
-  int G = 1;
-  const int rows = (h.Hu + h.oh - 1) / h.oh;
-  while (G * 2 * h.F <= 2 * HT && G * 2 <= rows) G *= 2;
-  const size_t lds = (size_t)(h.F + h.Cls + G * h.F + 8) * sizeof(float);
-  hipLaunchKernelGGL(head_fwd_kernel, dim3(h.B), dim3(HT), lds, st, h, U, labels, Wf, bf, Pq, dz, loss_n, G);
+hipError_t launch_head_pool(const HeadShape &h, const float *U, float *Pq, hipStream_t st) {
+  const dim3 grid((unsigned)(h.B * h.oh * h.ow));
+  if (h.A % 4 == 0)
+    hipLaunchKernelGGL(head_pool_kernel<4>, grid, dim3(HT), 0, st, h, U, Pq);
+  else
+    hipLaunchKernelGGL(head_pool_kernel<1>, grid, dim3(HT), 0, st, h, U, Pq);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
+                          const float *bf, float *dz, float *loss_n, hipStream_t st) {
+  const size_t lds = (size_t)(h.F + h.Cls + 8) * sizeof(float);
+  hipLaunchKernelGGL(head_fc_kernel, dim3(h.B), dim3(HT), lds, st, h, Pq, labels, Wf, bf, dz, loss_n);
   return hipGetLastError();
 }
 
@@ -219,9 +286,18 @@ hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, c
   return hipGetLastError();
 }
 
-hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU, hipStream_t st) {
-  const long long total = (long long)h.B * h.Hu * h.Wu * h.A;
-  hipLaunchKernelGGL(pool_relu_bwd_kernel, dim3((unsigned)((total + HT - 1) / HT)), dim3(HT), 0, st, h, U, dPq, dU);
+hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU, const float *Wa,
+                                float *WaT, int R, int S, int K, hipStream_t st) {
+  const int V = h.A % 4 == 0 ? 4 : 1;
+  const long long total = (long long)h.B * h.Hu * h.Wu * (h.A / V);
+  const int nb_main = (int)((total + HT - 1) / HT);
+  const int nb_t = Wa ? (int)(((long long)h.A * R * S * K + HT - 1) / HT) : 0;
+  if (V == 4)
+    hipLaunchKernelGGL(pool_relu_bwd_kernel<4>, dim3(nb_main + nb_t), dim3(HT), 0, st, h, U, dPq, dU, nb_main, Wa, WaT,
+                       R, S, K);
+  else
+    hipLaunchKernelGGL(pool_relu_bwd_kernel<1>, dim3(nb_main + nb_t), dim3(HT), 0, st, h, U, dPq, dU, nb_main, Wa, WaT,
+                       R, S, K);
   return hipGetLastError();
 }
 

@@ -266,7 +266,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_wgrad_kernel(WgradProblem p) {
 // Sum of the split partials in a fixed order.  A workgroup owns 256/ZS groups of four
 // consecutive elements of the flattened [P][Qld] tile array; its ZS thread rows each add every
 // ZS-th split with 16-byte loads, then the ZS row sums are added in order through LDS.  The
-// last workgroup does the same for the bias partials.
+// workgroups past `main_blocks` do the same for the bias partials.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part,
                                                            const float *__restrict__ part_b, int splits, int P, int Q,
                                                            int Qld, int Q0, float *__restrict__ out0,
@@ -307,9 +307,16 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
       }
     }
   } else if (ob) {
-    for (int pr = t; pr < P; pr += 256) {
-      float sb = 0.f;
-      for (int z = 0; z < splits; ++z) sb += part_b[(long long)z * P + pr];
+    // bias partials: each extra workgroup owns 16 columns, 16 thread rows add every 16th split
+    const int pr = ((int)blockIdx.x - main_blocks) * 16 + (t & 15), zb = t >> 4;
+    float sb = 0.f;
+    if (pr < P)
+      for (int z = zb; z < splits; z += 16) sb += part_b[(long long)z * P + pr];
+    float *redb = reinterpret_cast<float *>(red);
+    redb[t] = sb;
+    __syncthreads();
+    if (zb == 0 && pr < P) {
+      for (int k = 1; k < 16; ++k) sb += redb[k * 16 + (t & 15)];
       ob[pr] = sb;
     }
   }
@@ -377,7 +384,7 @@ hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int split
   const int cols = 256 / ZS;
   const long long n4 = ((long long)P * Qld) / 4;
   const int main_blocks = (int)((n4 + cols - 1) / cols);
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)(main_blocks + (ob ? 1 : 0))), dim3(256), 0, st, part, part_b,
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)(main_blocks + (ob ? (P + 15) / 16 : 0))), dim3(256), 0, st, part, part_b,
                      splits, P, Q, Qld, Q0, out0, out1, ob, ZS, main_blocks);
   return hipGetLastError();
 }

@@ -256,8 +256,9 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   if (rc) return rc;
   const HeadShape hs = head_shape(a, ad, B);
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
-  NF_RUN(st, "head_fwd", 2.0 * B * fc, 4.0 * (u + fc + (double)B * (ad.F + a->n_classes)),
-         launch_head_fwd(hs, wsf(ws, w.U), labels, ap->Wf, ap->bf, wsf(ws, w.Pq), wsf(ws, w.dz), wsf(ws, w.loss_n), st));
+  NF_RUN(st, "head_pool", 0.0, 4.0 * (u + (double)B * ad.F), launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.Pq), st));
+  NF_RUN(st, "head_fc", 2.0 * B * fc, 4.0 * ((double)B * fc + (double)B * (ad.F + a->n_classes)),
+         launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), st));
   NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
   return NF_OK;
 }
@@ -274,8 +275,9 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
   NF_RUN(st, "fc_bwd", 4.0 * B * fc, 4.0 * (2.0 * fc + (double)B * (2.0 * ad.F + a->n_classes)),
          launch_fc_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ap->Wf, ga->Wf, ga->bf, wsf(ws, w.dPq), st));
-  NF_RUN(st, "pool_relu_bwd", 0.0, 4.0 * (2.0 * u + (double)B * ad.F),
-         launch_pool_relu_bwd(hs, wsf(ws, w.U), wsf(ws, w.dPq), dU, st));
+  const double wa = (double)a->A * a->R * a->S * a->C_in;
+  NF_RUN(st, "pool_relu_bwd", 0.0, 4.0 * (2.0 * u + (double)B * ad.F) + 8.0 * wa,
+         launch_pool_relu_bwd(hs, wsf(ws, w.U), wsf(ws, w.dPq), dU, ap->Wa, wsf(ws, w.WaT), a->R, a->S, a->C_in, st));
   // beta_n: weight + bias gradient
   {
     WgradProblem g;
@@ -292,9 +294,6 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
   }
   // beta_n: data gradient w.r.t. the emitted activation, layer ReLU mask fused when un-pooled
   {
-    const double wa = (double)a->A * a->R * a->S * a->C_in;
-    NF_RUN(st, "flip_transpose", 0.0, 8.0 * wa,
-           launch_flip_transpose(ap->Wa, wsf(ws, w.WaT), a->A, a->R, a->S, a->C_in, st));
     FwdProblem f;
     std::memset((void *)&f, 0, sizeof(f));
     f.x = dU, f.w = wsf(ws, w.WaT);

@@ -67,13 +67,15 @@ hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int split
 struct HeadShape {
   int B, Hu, Wu, A, oh, ow, F, Cls, relu;
 };
-hipError_t launch_head_fwd(const HeadShape &h, const float *U, const int32_t *labels, const float *Wf,
-                           const float *bf, float *Pq, float *dz, float *loss_n, hipStream_t st);
+hipError_t launch_head_pool(const HeadShape &h, const float *U, float *Pq, hipStream_t st);
+hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
+                          const float *bf, float *dz, float *loss_n, hipStream_t st);
 hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStream_t st);
 hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, const float *Wf, float *dWf,
                          float *dbf, float *dPq, hipStream_t st);
-hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU,
-                                hipStream_t st);
+// also writes WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa is given
+hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU, const float *Wa,
+                                float *WaT, int R, int S, int K, hipStream_t st);
 
 // ---- elementwise / data movement ----
 hipError_t launch_flip_transpose(const float *Wa, float *WaT, int A, int R, int S, int K, hipStream_t st);
