@@ -352,15 +352,23 @@ hipError_t launch_cfg(const WgradProblem &p0, bool vec, hipStream_t st) {
 
 int wgrad_pick_splits(int P, int Q, int M) {
   const TileChoice tc = pick_tile(P);
-  const long long tiles = (long long)((P + tc.BP - 1) / tc.BP) * ((Q + tc.BQ - 1) / tc.BQ);
-  // Two workgroups fit on a compute unit (LDS), 256 CUs: aim at <= 512 workgroups that are all
-  // resident at once, and keep at least 4 staging steps per split.  Every workgroup writes its
-  // tile once, so fewer splits also means less partial-sum traffic.
-  long long want = 512 / tiles;
+  const long long tp = (P + tc.BP - 1) / tc.BP, tq = (Q + tc.BQ - 1) / tc.BQ, tiles = tp * tq;
+  // Cost model in microseconds, minimised over the split count S (at least 4 staging steps per
+  // split).  Two workgroups fit on a compute unit (LDS) and run best as a pair (measured: one
+  // per CU is ~1.6x slower), the chip has 256 CUs: workgroups execute in rounds of 512, and a
+  // partly filled round costs as much as a full one.  MFMA time = padded work at ~100 TFLOP/s
+  // times rounds*512/workgroups.  Every workgroup writes its tile once and the reduction reads
+  // it back: 8 bytes per partial element at ~3 TB/s.
+  const double work_us = 2.0 * M * (double)(tp * tc.BP) * (double)(tq * tc.BQ) / 100e12 * 1e6;
   const long long max_by_m = (M + 4 * BKM - 1) / (4 * BKM);
-  if (want > max_by_m) want = max_by_m;
-  if (want < 1) want = 1;
-  return (int)want;
+  long long best = 1;
+  double best_cost = 1e30;
+  for (long long S = 1; S <= max_by_m && S <= 512; ++S) {
+    const long long wgs = tiles * S, rounds = (wgs + 511) / 512;
+    const double cost = work_us * (double)(rounds * 512) / (double)wgs + 8.0 * (double)S * P * Q / 3e12 * 1e6;
+    if (cost < best_cost) best_cost = cost, best = S;
+  }
+  return (int)best;
 }
 
 hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char **kernel) {
