@@ -318,7 +318,7 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
   q.xs_bytes = p.Cs ? (uint32_t)(B * p.Hs * p.Ws * p.Cs * 4) : 0;
   q.wp_bytes = p.Cs ? (uint32_t)((long long)p.N * p.Cs * 4) : 0;
   q.nkb_conv = q.nkb_proj = 0;  // set per tile configuration
-  if (p.N > 64) {
+  if (p.N > 64 && p.Kg > 160) {
     *kernel = "igemm_fwd_fast_128x128";
     return launch_cfg<128, 128, 32, 2, 2, 32>(p, q, st);
   }
@@ -331,7 +331,9 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
     return launch_cfg<128, 32, 32, 4, 1, 32>(p, q, st);
   }
   *kernel = "igemm_fwd_fast_64x16";
-  return launch_cfg<64, 16, 128, 4, 1, 16>(p, q, st);
+  // long reductions: fewer, longer steps (the step cost of this tile is mostly the barrier)
+  if (p.Kg > 1536) return launch_cfg<64, 16, 64, 4, 1, 16>(p, q, st);
+  return launch_cfg<64, 16, 32, 4, 1, 16>(p, q, st);
 }
 
 }  // namespace nf
