@@ -26,51 +26,90 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
-// F_n: adaptive average pool.  One workgroup per (sample, output cell); its threads are
-// CA channel groups (V channels each, 16-byte loads when V == 4) x NS window-position slices;
-// slice sums are added in order through LDS.
+// F_n: adaptive average pool.  A workgroup serves G (sample, output cell) pairs; each pair has
+// CA channel lanes (V channels each, 16-byte accesses when V == 4) x NS window-position slices,
+// CA * NS * G = HT.  Slice sums are added in order through LDS.
+// With splits > 0 the aux activation does not exist yet: it is formed here from the raw partial
+// sums of the split aux convolution, U = act(sum_z part[z] + ba), and written out on the way.
 template <int V>
-__global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, const float *__restrict__ U,
-                                                       float *__restrict__ Pq) {
+__global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__restrict__ U,
+                                                       const float *__restrict__ part, int splits,
+                                                       const float *__restrict__ ba, float *__restrict__ Pq,
+                                                       int CA, int NS) {
   __shared__ float red[HT * V];
   const int t = threadIdx.x;
-  const int n = blockIdx.x / (s.oh * s.ow), cell = blockIdx.x % (s.oh * s.ow);
+  const int per = CA * NS, G = HT / per;
+  const int grp = t / per, tg = t - grp * per;
+  const int lane = tg % CA, slice = tg / CA;
+  const int cells = s.oh * s.ow;
+  const long long pair = (long long)blockIdx.x * G + grp;
+  const bool live = grp < G && pair < (long long)s.B * cells;
+  const int n = live ? (int)(pair / cells) : 0, cell = live ? (int)(pair - (long long)n * cells) : 0;
   const int ci = cell / s.ow, cj = cell - ci * s.ow;
   int h0, h1, w0, w1;
   adaptive_window(ci, s.Hu, s.oh, h0, h1);
   adaptive_window(cj, s.Wu, s.ow, w0, w1);
   const int ww = w1 - w0, npos = (h1 - h0) * ww;
   const int AV = s.A / V;
-  const int CA = AV < HT ? AV : HT, NS = HT / CA;
-  const int lane = t % CA, slice = t / CA;
   const float inv = 1.f / (float)npos;
-  const float *Un = U + (long long)n * s.Hu * s.Wu * s.A;
+  const long long total = (long long)s.B * s.Hu * s.Wu * s.A;
   for (int c0 = 0; c0 < AV; c0 += CA) {
     const int col = c0 + lane;
     float acc[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) acc[e] = 0.f;
-    if (col < AV && slice < NS) {
+    if (live && col < AV) {
+      float bias[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) bias[e] = (splits > 0 && ba) ? ba[col * V + e] : 0.f;
+#pragma unroll 4
       for (int pos = slice; pos < npos; pos += NS) {
         const int hh = h0 + pos / ww, wx = w0 + pos % ww;
-        const float *src = Un + ((long long)hh * s.Wu + wx) * s.A + col * V;
-        if constexpr (V == 4) {
-          const float4 v = *reinterpret_cast<const float4 *>(src);
-          acc[0] += v.x, acc[1] += v.y, acc[2] += v.z, acc[3] += v.w;
+        const long long at = (((long long)n * s.Hu + hh) * s.Wu + wx) * s.A + col * V;
+        float v[V];
+        if (splits > 0) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) v[e] = 0.f;
+          for (int z = 0; z < splits; ++z) {
+            const float *src = part + (long long)z * total + at;
+            if constexpr (V == 4) {
+              const float4 x = *reinterpret_cast<const float4 *>(src);
+              v[0] += x.x, v[1] += x.y, v[2] += x.z, v[3] += x.w;
+            } else {
+              v[0] += src[0];
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < V; ++e) {
+            v[e] += bias[e];
+            if (s.relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
+          }
+          if constexpr (V == 4) {
+            *reinterpret_cast<float4 *>(U + at) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            U[at] = v[0];
+          }
         } else {
-          acc[0] += src[0];
+          if constexpr (V == 4) {
+            const float4 x = *reinterpret_cast<const float4 *>(U + at);
+            v[0] = x.x, v[1] = x.y, v[2] = x.z, v[3] = x.w;
+          } else {
+            v[0] = U[at];
+          }
         }
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += v[e];
       }
     }
     __syncthreads();  // previous round's reads of red are done
 #pragma unroll
     for (int e = 0; e < V; ++e) red[t * V + e] = acc[e];
     __syncthreads();
-    if (slice == 0 && col < AV) {
+    if (live && slice == 0 && col < AV) {
 #pragma unroll
       for (int e = 0; e < V; ++e) {
         float sum = acc[e];
-        for (int k = 1; k < NS; ++k) sum += red[(k * CA + lane) * V + e];
+        for (int k = 1; k < NS; ++k) sum += red[(grp * per + k * CA + lane) * V + e];
         Pq[(long long)n * s.F + cell * s.A + col * V + e] = sum * inv;
       }
     }
@@ -253,12 +292,23 @@ __global__ __launch_bounds__(HT) void pool_relu_bwd_kernel(HeadShape s, const fl
 
 }  // namespace
 
-hipError_t launch_head_pool(const HeadShape &h, const float *U, float *Pq, hipStream_t st) {
-  const dim3 grid((unsigned)(h.B * h.oh * h.ow));
-  if (h.A % 4 == 0)
-    hipLaunchKernelGGL(head_pool_kernel<4>, grid, dim3(HT), 0, st, h, U, Pq);
+hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
+                            hipStream_t st) {
+  const int V = h.A % 4 == 0 ? 4 : 1;
+  const int AV = h.A / V;
+  int CA = 1;
+  while (CA < AV && CA < HT) CA *= 2;  // channel lanes: power of two covering A / V (or all threads)
+  // largest pooling window -> position slices (power of two, at most what the workgroup has left)
+  const int wh = (h.Hu + h.oh - 1) / h.oh + (h.Hu % h.oh ? 1 : 0), wwid = (h.Wu + h.ow - 1) / h.ow + (h.Wu % h.ow ? 1 : 0);
+  int NS = 1;
+  while (NS * 2 <= wh * wwid && CA * NS * 2 <= HT) NS *= 2;
+  const int G = HT / (CA * NS);
+  const long long pairs = (long long)h.B * h.oh * h.ow;
+  const dim3 grid((unsigned)((pairs + G - 1) / G));
+  if (V == 4)
+    hipLaunchKernelGGL(head_pool_kernel<4>, grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, CA, NS);
   else
-    hipLaunchKernelGGL(head_pool_kernel<1>, grid, dim3(HT), 0, st, h, U, Pq);
+    hipLaunchKernelGGL(head_pool_kernel<1>, grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, CA, NS);
   return hipGetLastError();
 }
 

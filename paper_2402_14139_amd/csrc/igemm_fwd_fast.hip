@@ -31,6 +31,7 @@ struct FastAux {
   FastDiv div_c, div_s;
   uint32_t x_bytes, w_bytes, xs_bytes, wp_bytes;
   int nkb_conv, nkb_proj;
+  int kb_per;  // reduction steps per split (gridDim.y splits; every split but the last gets this many)
 };
 
 __device__ inline float4 bload(__amdgpu_buffer_rsrc_t r, int voff) {
@@ -123,7 +124,9 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
 
   // Two register sets of staged chunks: global loads run two reduction steps ahead of the MFMAs.
   float4 ra[2][PA], rb[2][PB];
-  const int nkb = q.nkb_conv + q.nkb_proj;
+  // this workgroup's share of the reduction: steps [kb0, kb_end)
+  const int kb0 = blockIdx.y * q.kb_per;
+  const int kb_end = min(q.nkb_conv + q.nkb_proj, kb0 + q.kb_per);
 
   // Branch-free gather of step kb into register set `set`.  Steps past the end, the padding of the
   // reduction axis, taps outside the image and rows past M or N all become the out-of-range
@@ -131,7 +134,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   // through a uniform select of the buffer descriptor.
   auto gload = [&](int kb, int set) {
     const int kg = kb * BK + ch * 4;
-    const bool in = kg < p.RSC;
+    const bool in = kg < p.RSC && kb < kb_end;
     const int tap = in ? (int)q.div_c.div((uint32_t)kg) : 0;
     const int c = kg - tap * p.C;
     const int r = (int)q.div_s.div((uint32_t)tap);
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
     if constexpr (PROJ) {
       const bool is_proj = kb >= q.nkb_conv;  // uniform
       const int cp = (kb - q.nkb_conv) * BK + ch * 4;
-      const bool inp = is_proj && cp < p.Cs;
+      const bool inp = is_proj && cp < p.Cs && kb < kb_end;
 #pragma unroll
       for (int i = 0; i < PA; ++i) offa[i] = is_proj ? ((inp && sbase[i] != OOB) ? sbase[i] + cp * 4 : OOB) : offa[i];
 #pragma unroll
@@ -252,14 +255,32 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
     }
   };
 
-  gload(0, 0);
+  gload(kb0, 0);
   lstore(0, 0);
-  gload(1, 1);
+  gload(kb0 + 1, 1);
   __syncthreads();
   lfrag(0, 0, 0);
-  for (int kb = 0; kb < nkb; kb += 2) {
+  for (int kb = kb0; kb < kb_end; kb += 2) {
     step(kb, std::integral_constant<int, 0>{});
-    if (kb + 1 < nkb) step(kb + 1, std::integral_constant<int, 1>{});
+    if (kb + 1 < kb_end) step(kb + 1, std::integral_constant<int, 1>{});
+  }
+
+  // ---- split reduction: raw partial sums, slice blockIdx.y of out[splits][M][N] ----
+  if (gridDim.y > 1) {
+    float *part = p.out + (long long)blockIdx.y * p.M * p.N;
+#pragma unroll
+    for (int b = 0; b < NT; ++b) {
+      const int n = n0 + wn * TN + b * MF + j;
+      if (n >= p.N) continue;
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int e = 0; e < MM::NACC; ++e) {
+          const int m = m0 + wm * TM + a * MF + MM::row(e, g);
+          if (m < p.M) part[(long long)m * p.N + n] = acc[a][b][e];
+        }
+    }
+    return;
   }
 
   // ---- epilogue: bias, identity shortcut, ReLU, mask; consecutive lanes store consecutive n ----
@@ -291,14 +312,31 @@ hipError_t launch_cfg(const FwdProblem &p, FastAux q, hipStream_t st) {
   constexpr bool SCHED = MF == 32;
   q.nkb_conv = (p.RSC + BK - 1) / BK;
   q.nkb_proj = p.Cs ? (p.Cs + BK - 1) / BK : 0;
+  const int nkb = q.nkb_conv + q.nkb_proj;
+  const int splits = p.ksplits > 1 ? p.ksplits : 1;
+  q.kb_per = (nkb + splits - 1) / splits;
+  const dim3 grid((unsigned)tiles, (unsigned)splits);
   if (q.nkb_proj)
-    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, true, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, true, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
   else
-    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, false, SCHED>), dim3(tiles), dim3(WM * WN * 64), 0, st, p, q);
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, false, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
   return hipGetLastError();
 }
 
 }  // namespace
+
+// Skinny outputs (few filters) with a long reduction leave most of the chip idle: M/64 or M/128
+// workgroups, each a long serial chain of load -> LDS -> MFMA steps.  Splitting the reduction
+// multiplies the workgroups; the consumer adds the partial sums in a fixed order.
+int igemm_fwd_pick_ksplits(int M, int N, int RSC, int C, int taps) {
+  if (C % 4 || taps > 32 || N > 32) return 1;
+  const int tiles = N > 16 ? (M + 127) / 128 : (M + 63) / 64;
+  const int nkb = (RSC + 31) / 32;
+  int s = 1024 / (tiles > 0 ? tiles : 1);
+  if (s > nkb / 16) s = nkb / 16;
+  if (s > 16) s = 16;
+  return s > 1 ? s : 1;
+}
 
 bool igemm_fwd_fast_applicable(const FwdProblem &p) {
   const long long lim = 0x7FFFFFF0ll;
@@ -322,6 +360,11 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
     *kernel = "igemm_fwd_fast_128x128";
     return launch_cfg<128, 128, 32, 2, 2, 32>(p, q, st);
   }
+  if (p.N > 32 && p.Kg <= 160) {
+    // one to five reduction steps: bound by the output stream; small tiles keep more waves in flight
+    *kernel = "igemm_fwd_fast_64x64";
+    return launch_cfg<64, 64, 32, 2, 2, 32>(p, q, st);
+  }
   if (p.N > 32) {
     *kernel = "igemm_fwd_fast_128x64";
     return launch_cfg<128, 64, 32, 2, 2, 32>(p, q, st);
@@ -331,6 +374,7 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
     return launch_cfg<128, 32, 32, 4, 1, 32>(p, q, st);
   }
   *kernel = "igemm_fwd_fast_64x16";
+  if (p.ksplits > 1) return launch_cfg<64, 16, 32, 4, 1, 16>(p, q, st);
   // long reductions: fewer, longer steps (the step cost of this tile is mostly the barrier)
   if (p.Kg > 1536) return launch_cfg<64, 16, 64, 4, 1, 16>(p, q, st);
   return launch_cfg<64, 16, 32, 4, 1, 16>(p, q, st);

@@ -87,6 +87,7 @@ int32_t check_sizes(const nf_layer_desc *d, const LayerDims &ld, int32_t B) {
 struct WsLayout {
   size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
+  int ksplits_aux;  // reduction splits of the aux convolution forward (partials alias `part`)
 };
 
 WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B) {
@@ -120,7 +121,11 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     w.splits_aux = wgrad_pick_splits(a->A, Qa, B * ad.Hu * ad.Wu);
     w.splits_layer = wgrad_pick_splits(d->C_out, Ql, B * ld.Ho * ld.Wo);
     const size_t pa = (size_t)w.splits_aux * a->A * w.Qld_aux, pl = (size_t)w.splits_layer * d->C_out * w.Qld_layer;
-    w.part = take((pa > pl ? pa : pl) * f);
+    w.ksplits_aux = igemm_fwd_pick_ksplits(B * ad.Hu * ad.Wu, a->A, Qa, a->C_in, a->R * a->S);
+    const size_t pk = w.ksplits_aux > 1 ? (size_t)w.ksplits_aux * u : 0;
+    size_t pmax = pa > pl ? pa : pl;
+    if (pk > pmax) pmax = pk;
+    w.part = take(pmax * f);
     const size_t ba = (size_t)w.splits_aux * a->A, bl = (size_t)w.splits_layer * d->C_out;
     w.part_b = take((ba > bl ? ba : bl) * f);
   }
@@ -251,12 +256,16 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   f.relu = a->relu ? 1 : 0;
   f.M = B * ad.Hu * ad.Wu, f.RSC = a->R * a->S * a->C_in, f.Kg = f.RSC;
   f.div_howo = FastDiv(ad.Hu * ad.Wu), f.div_wo = FastDiv(ad.Wu);
-  f.out = wsf(ws, w.U);
+  // skinny head, long reduction: split it; the pooling kernel adds the parts, bias and ReLU
+  const int ks = (w.ksplits_aux > 1 && igemm_fwd_fast_applicable(f)) ? w.ksplits_aux : 0;
+  f.ksplits = ks;
+  f.out = ks ? wsf(ws, w.part) : wsf(ws, w.U);
   int32_t rc = enqueue_fwd(f, st);
   if (rc) return rc;
   const HeadShape hs = head_shape(a, ad, B);
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
-  NF_RUN(st, "head_pool", 0.0, 4.0 * (u + (double)B * ad.F), launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.Pq), st));
+  NF_RUN(st, "head_pool", 0.0, 4.0 * (u * (ks ? ks + 1.0 : 1.0) + (double)B * ad.F),
+         launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.part), ks, ap->ba, wsf(ws, w.Pq), st));
   NF_RUN(st, "head_fc", 2.0 * B * fc, 4.0 * ((double)B * fc + (double)B * (ad.F + a->n_classes)),
          launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), st));
   NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));

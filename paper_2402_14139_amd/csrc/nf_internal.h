@@ -36,7 +36,12 @@ struct FwdProblem {
   int relu;
   int M, RSC, Kg;
   FastDiv div_howo, div_wo;
+  // > 1: the reduction is cut into this many parts and `out` is [ksplits][M][N] raw partial sums
+  // (no bias, shortcut, ReLU or mask); only with a value igemm_fwd_pick_ksplits returned
+  int ksplits;
 };
+// how many reduction splits a skinny forward-type contraction should use (1 = none)
+int igemm_fwd_pick_ksplits(int M, int N, int RSC, int C, int taps);
 // `*kernel` receives a static string naming the tile configuration that was launched
 hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **kernel);
 // branch-free buffer-load variant (igemm_fwd_fast.hip); launch_igemm_fwd picks it when applicable
@@ -67,7 +72,10 @@ hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int split
 struct HeadShape {
   int B, Hu, Wu, A, oh, ow, F, Cls, relu;
 };
-hipError_t launch_head_pool(const HeadShape &h, const float *U, float *Pq, hipStream_t st);
+// Pq = adaptive average pool of U.  With splits > 0, U is first formed from the raw partial sums
+// part[splits][B*Hu*Wu*A] of the aux convolution: U = act(sum_z part[z] + ba) (written out).
+hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
+                            hipStream_t st);
 hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
                           const float *bf, float *dz, float *loss_n, hipStream_t st);
 hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStream_t st);
