@@ -296,7 +296,7 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     g.Wo = ad.Wu;
     g.P = a->A, g.M = B * ad.Hu * ad.Wu, g.RSC = a->R * a->S * a->C_in, g.Q = g.RSC, g.Qld = w.Qld_aux;
     g.splits = w.splits_aux;
-    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;
+    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
     g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);
     const int32_t rc = enqueue_wgrad(g, ga->Wa, nullptr, ga->ba, st);
     if (rc) return rc;
@@ -331,7 +331,7 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     if (d->skip_kind == 2) g.xs = xs, g.Cs = d->skip_C, g.Hs = d->skip_H, g.Ws = d->skip_W, g.ss = d->skip_stride;
     g.P = d->C_out, g.M = B * ld.Ho * ld.Wo, g.RSC = d->R * d->S * d->C_in, g.Q = g.RSC + g.Cs, g.Qld = w.Qld_layer;
     g.splits = w.splits_layer;
-    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;
+    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
     g.div_howo = FastDiv(ld.Ho * ld.Wo), g.div_wo = FastDiv(ld.Wo);
     const int32_t rc = enqueue_wgrad(g, gp->W, gp->Wp, gp->b, st);
     if (rc) return rc;

@@ -63,6 +63,9 @@ struct WgradProblem {
 // chooses the tile shape for (P,Q); reports how many splits of M it wants
 int wgrad_pick_splits(int P, int Q, int M);
 hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char **kernel);
+// software-pipelined buffer-load variant (igemm_wgrad_fast.hip); launch_igemm_wgrad picks it when applicable
+bool igemm_wgrad_fast_applicable(const WgradProblem &p);
+hipError_t launch_igemm_wgrad_fast(const WgradProblem &p, hipStream_t st, const char **kernel);
 // out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length Q-Q0) = sum_z part[z][p][q];
 // ob[p] = sum_z part_b[z][p]
 hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int splits, int P, int Q, int Qld,
