@@ -67,6 +67,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
 
   __shared__ __attribute__((aligned(16))) float Ds[2][BKM][LDP];
   __shared__ __attribute__((aligned(16))) float Xs[2][BKM][LDQ];
+  __shared__ int4 Rt[2][BKM];
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
@@ -105,29 +106,44 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   const bool do_bias = (blockIdx.x == 0) && (p.part_b != nullptr);
   const float bsel = do_bias ? 1.f : 0.f;
 
-  // Branch-free gather of staging step `s` into register set `set`.
+  // Row table: entry r of Rt[s & 1] describes reduction row m_begin + 32*s + r of staging step s:
+  // {byte offset of its receptive field's corner in x, hi0, wi0, byte offset of its pixel in the
+  // projection input}; hi0 is far negative for rows past the split.  Every thread decodes ONE row
+  // per step (threads with equal t & 31 write the same entry) instead of its NQ rows.
+  auto rt_make = [&](int s) {
+    const int m = m_begin + s * BKM + (t & (BKM - 1));
+    const int img = (int)p.div_howo.div((uint32_t)m);
+    const int rem = m - img * p.Ho * p.Wo;
+    const int ho = (int)p.div_wo.div((uint32_t)rem);
+    const int wo = rem - ho * p.Wo;
+    const int hi0 = ho * p.stride - p.pad, wi0 = wo * p.stride - p.pad;
+    int4 e;
+    e.x = ((img * p.H + hi0) * p.W + wi0) * p.C * 4;
+    e.y = m < m_end ? hi0 : -(1 << 20);
+    e.z = wi0;
+    e.w = PROJ ? ((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs * 4 : 0;
+    Rt[s & 1][t & (BKM - 1)] = e;
+  };
+
+  // Branch-free gather of staging step `s` into register set `set` (reads Rt[s & 1]).
   auto gload = [&](int s, int set) {
     const int mb = m_begin + s * BKM;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int m = mb + rowp + RP * i;
       const bool ok = (m < m_end) & (dcol_off != OOB);
-      rd[set][i] = bload(rsd, ok ? m * p.P * 4 + dcol_off : OOB);
+      rd[set][i] = bload(rsd, (m * p.P * 4 + dcol_off) | (ok ? 0 : OOB));
     }
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-      const int m = mb + rowq + RQ * i;
-      const int img = (int)p.div_howo.div((uint32_t)m);
-      const int rem = m - img * p.Ho * p.Wo;
-      const int ho = (int)p.div_wo.div((uint32_t)rem);
-      const int wo = rem - ho * p.Wo;
-      const int hi0 = ho * p.stride - p.pad, wi0 = wo * p.stride - p.pad;
-      // bitwise &: no short-circuit, so the decode above is not sunk into branches
-      const bool ok = (m < m_end) & is_tap & ((unsigned)(hi0 + qr) < (unsigned)p.H) & ((unsigned)(wi0 + qs) < (unsigned)p.W);
-      float4 v = bload(rsx, ok ? ((img * p.H + hi0) * p.W + wi0) * p.C * 4 + xtap_off : OOB);
+      const int4 e = Rt[s & 1][rowq + RQ * i];
+      const bool ok = is_tap & ((unsigned)(e.y + qr) < (unsigned)p.H) & ((unsigned)(e.z + qs) < (unsigned)p.W);
+      // the offset is formed unconditionally and pushed out of range by its top bit: a select would
+      // let the compiler sink the table read into a branch
+      float4 v = bload(rsx, (e.x + xtap_off) | (ok ? 0 : OOB));
       if constexpr (PROJ) {
-        const bool okp = (m < m_end) & is_proj;
-        const float4 u = bload(rsxs, okp ? (((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs + qc) * 4 : OOB);
+        const bool okp = is_proj & (e.y > -(1 << 19));
+        const float4 u = bload(rsxs, (e.w + qc * 4) | (okp ? 0 : OOB));
         v.x += u.x, v.y += u.y, v.z += u.z, v.w += u.w;  // one of the two is all zeros
       }
       rx[set][i] = v;
@@ -183,6 +199,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   auto step = [&](int s, auto par_tag) {
     constexpr int par = decltype(par_tag)::value;
     gload(s + 2, par);  // set `par` held step s, already in LDS
+    rt_make(s + 3);     // other table buffer than the one gload(s + 2) reads
 #pragma unroll
     for (int ss = 0; ss + 1 < NSS; ++ss) {
       lfrag(par, ss + 1, (ss + 1) & 1);
@@ -216,9 +233,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   };
 
   const int nsteps = (m_end - m_begin + BKM - 1) / BKM;
+  rt_make(0);
+  rt_make(1);
+  __syncthreads();
   gload(0, 0);
   lstore(0, 0);
   gload(1, 1);
+  __syncthreads();  // table reads done
+  rt_make(2);
   __syncthreads();
   lfrag(0, 0, 0);
   // unconditional pairs: an odd count runs one step of zeros (rows past m_end load zeros)
