@@ -100,21 +100,6 @@ __global__ __launch_bounds__(ET) void maxpool_bwd_kernel(const float *__restrict
   }
 }
 
-// WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k]
-__global__ __launch_bounds__(ET) void flip_transpose_kernel(const float *__restrict__ Wa, float *__restrict__ WaT,
-                                                            int A, int R, int S, int K) {
-  const long long total = (long long)A * R * S * K;
-  const long long i = (long long)blockIdx.x * ET + threadIdx.x;
-  if (i >= total) return;
-  const int a = (int)(i % A);
-  long long r = i / A;
-  const int s = (int)(r % S);
-  r /= S;
-  const int rr = (int)(r % R);
-  const int k = (int)(r / R);
-  WaT[i] = Wa[(((long long)a * R + (R - 1 - rr)) * S + (S - 1 - s)) * K + k];
-}
-
 // ---- update line of Algorithm 2: blockIdx.y = tensor, grid-stride over its elements ----
 __global__ __launch_bounds__(ET) void sgd_kernel(SgdTensors t) {
   const int ti = blockIdx.y;
@@ -173,12 +158,6 @@ __global__ __launch_bounds__(ET) void cache_copy_kernel(const float *__restrict_
 inline unsigned nblocks(long long total) { return (unsigned)((total + ET - 1) / ET); }
 
 }  // namespace
-
-hipError_t launch_flip_transpose(const float *Wa, float *WaT, int A, int R, int S, int K, hipStream_t st) {
-  hipLaunchKernelGGL(flip_transpose_kernel, dim3(nblocks((long long)A * R * S * K)), dim3(ET), 0, st, Wa, WaT, A, R,
-                     S, K);
-  return hipGetLastError();
-}
 
 hipError_t launch_maxpool_fwd(const float *T, float *Y, uint8_t *arg, int B, int Ho, int Wo, int K, int Hp, int Wp,
                               int pk, int ps, int pp, hipStream_t st) {

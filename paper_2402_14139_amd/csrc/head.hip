@@ -117,11 +117,14 @@ __global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__res
 }
 
 // gamma_n and Eq. 3 for one sample per workgroup: logits (one thread per class, the pooled
-// features staged in LDS), log-sum-exp, per-sample loss, dL/dz.  Dynamic LDS: F + Cls + 8 floats.
+// features staged in LDS), log-sum-exp, per-sample loss, dL/dz, and -- the sample's dz being at
+// hand -- the gradient w.r.t. the pooled features dPq[n][f] = sum_q dz[n][q] * Wf[q][f].
+// Dynamic LDS: F + Cls + 8 floats.
 __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *__restrict__ Pq,
                                                      const int32_t *__restrict__ labels,
                                                      const float *__restrict__ Wf, const float *__restrict__ bf,
-                                                     float *__restrict__ dz, float *__restrict__ loss_n) {
+                                                     float *__restrict__ dz, float *__restrict__ loss_n,
+                                                     float *__restrict__ dPq) {
   extern __shared__ float sm[];
   float *pq = sm;           // [F]
   float *z = pq + s.F;      // [Cls]
@@ -160,14 +163,25 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
   const float lse = m + logf(se);
   const int y = labels[n];
   const float invB = 1.f / (float)s.B;
-  for (int q = t; q < s.Cls; q += HT) dz[(long long)n * s.Cls + q] = (expf(z[q] - lse) - (q == y ? 1.f : 0.f)) * invB;
-  if (t == 0) loss_n[n] = lse - ((y >= 0 && y < s.Cls) ? z[y] : 0.f);
+  const float zy = (y >= 0 && y < s.Cls) ? z[y] : 0.f;
+  __syncthreads();  // every read of the logits is done: z[] becomes dz[]
+  for (int q = t; q < s.Cls; q += HT) {
+    const float d = (expf(z[q] - lse) - (q == y ? 1.f : 0.f)) * invB;
+    dz[(long long)n * s.Cls + q] = d;
+    z[q] = d;
+  }
+  if (t == 0) loss_n[n] = lse - zy;
+  __syncthreads();
+  for (int f = t; f < s.F; f += HT) {
+    float acc = 0.f;
+#pragma unroll 4
+    for (int q = 0; q < s.Cls; ++q) acc += z[q] * Wf[(long long)q * s.F + f];
+    dPq[(long long)n * s.F + f] = acc;
+  }
 }
 
-// batch mean of the per-sample losses, fixed order
-__global__ __launch_bounds__(HT) void loss_mean_kernel(const float *__restrict__ loss_n, int B,
-                                                       float *__restrict__ out) {
-  __shared__ float red[HT];
+// batch mean of the per-sample losses, fixed order (one workgroup)
+__device__ inline void loss_mean_block(const float *__restrict__ loss_n, int B, float *__restrict__ out, float *red) {
   float acc = 0.f;
   for (int i = threadIdx.x; i < B; i += HT) acc += loss_n[i];
   red[threadIdx.x] = acc;
@@ -178,26 +192,44 @@ __global__ __launch_bounds__(HT) void loss_mean_kernel(const float *__restrict__
   }
   if (threadIdx.x == 0) *out = red[0] / (float)B;
 }
+__global__ __launch_bounds__(HT) void loss_mean_kernel(const float *__restrict__ loss_n, int B,
+                                                       float *__restrict__ out) {
+  __shared__ float red[HT];
+  loss_mean_block(loss_n, B, out, red);
+}
 
-// gamma_n backward in one launch:
-//   blocks [0, nb_w)          one class q and one chunk of `fch` features: the 256 threads are
-//                             fch feature lanes x (256/fch) batch slices; slice sums are added in
-//                             order through LDS.  dWf[q][f] = sum_n dz[n][q] * Pq[n][f];
-//                             chunk 0 also forms dbf[q] = sum_n dz[n][q].
-//   blocks [nb_w, nb_w+nb_p)  dPq[n][f] = sum_q dz[n][q] * Wf[q][f], one thread per element
-__global__ __launch_bounds__(HT) void fc_bwd_kernel(HeadShape s, const float *__restrict__ Pq,
-                                                    const float *__restrict__ dz, const float *__restrict__ Wf,
-                                                    float *__restrict__ dWf, float *__restrict__ dbf,
-                                                    float *__restrict__ dPq, int nb_w, int fch, int nchunks) {
+// Backward of the head after the softmax in one launch (gradient line of Algorithm 2); the
+// workgroup index selects the job:
+//   [0, nb_w)   gamma_n: one class q and one chunk of `fch` features; the 256 threads are fch
+//               feature lanes x (256/fch) batch slices, slice sums added in order through LDS.
+//               dWf[q][f] = sum_n dz[n][q] * Pq[n][f]; chunk 0 also forms dbf[q] = sum_n dz[n][q].
+//   then nb_u   F_n backward + aux ReLU mask: dU = [U > 0] * sum over windows containing (h,w)
+//               of dPq / |window|, V channels per thread;
+//   then nb_t   re-lay of the aux filter for the data gradient: WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k];
+//   then 0/1    batch mean of the per-sample losses (when loss_out is given).
+struct HeadBwdJobs {
+  int nb_w, nb_u, nb_t, fch, nchunks;
+};
+template <int V>
+__global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs jb, const float *__restrict__ Pq,
+                                                      const float *__restrict__ dz, float *__restrict__ dWf,
+                                                      float *__restrict__ dbf, const float *__restrict__ U,
+                                                      const float *__restrict__ dPq, float *__restrict__ dU,
+                                                      const float *__restrict__ Wa, float *__restrict__ WaT, int R,
+                                                      int S, int K, const float *__restrict__ loss_n,
+                                                      float *__restrict__ loss_out) {
   __shared__ float red[HT];
   __shared__ float redb[HT];
-  const int b = blockIdx.x, t = threadIdx.x;
-  if (b < nb_w) {
+  int b = blockIdx.x;
+  const int t = threadIdx.x;
+  if (b < jb.nb_w) {
+    const int fch = jb.fch, nchunks = jb.nchunks;
     const int q = b / nchunks, chunk = b - q * nchunks;
     const int fl = t % fch, ns = t / fch, NS = HT / fch;
     const int f = chunk * fch + fl;
     float acc = 0.f, bsum = 0.f;
     if (f < s.F) {
+#pragma unroll 4
       for (int n = ns; n < s.B; n += NS) {
         const float d = dz[(long long)n * s.Cls + q];
         bsum += d;
@@ -215,27 +247,58 @@ __global__ __launch_bounds__(HT) void fc_bwd_kernel(HeadShape s, const float *__
       for (int k = 1; k < NS; ++k) bsum += redb[k * fch];
       dbf[q] = bsum;
     }
-  } else {
-    const long long i = (long long)(b - nb_w) * HT + t;
-    if (i >= (long long)s.B * s.F) return;
-    const int n = (int)(i / s.F), f = (int)(i - (long long)n * s.F);
-    float acc = 0.f;
-    for (int q = 0; q < s.Cls; ++q) acc += dz[(long long)n * s.Cls + q] * Wf[(long long)q * s.F + f];
-    dPq[i] = acc;
+    return;
   }
-}
-
-// F_n backward + the aux ReLU mask: dU = [U > 0] * sum over windows containing (h,w) of dPq / |window|,
-// V channels per thread.  Workgroups past `nb_main` re-lay the aux filter for the data gradient:
-// WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] (same launch: one kernel less per step).
-template <int V>
-__global__ __launch_bounds__(HT) void pool_relu_bwd_kernel(HeadShape s, const float *__restrict__ U,
-                                                           const float *__restrict__ dPq, float *__restrict__ dU,
-                                                           int nb_main, const float *__restrict__ Wa,
-                                                           float *__restrict__ WaT, int R, int S, int K) {
-  if ((int)blockIdx.x >= nb_main) {
+  b -= jb.nb_w;
+  if (b < jb.nb_u) {
+    const int AV = s.A / V;
+    const long long total = (long long)s.B * s.Hu * s.Wu * AV;
+    const long long i = (long long)b * HT + t;
+    if (i >= total) return;
+    const int av = (int)(i % AV);
+    long long r = i / AV;
+    const int w = (int)(r % s.Wu);
+    r /= s.Wu;
+    const int hh = (int)(r % s.Hu);
+    const int n = (int)(r / s.Hu);
+    const long long e0 = i * V;
+    float u[V], acc[V];
+    if constexpr (V == 4) {
+      const float4 t4 = *reinterpret_cast<const float4 *>(U + e0);
+      u[0] = t4.x, u[1] = t4.y, u[2] = t4.z, u[3] = t4.w;
+    } else {
+      u[0] = U[e0];
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    for (int ci = 0; ci < s.oh; ++ci) {
+      int h0, h1;
+      adaptive_window(ci, s.Hu, s.oh, h0, h1);
+      if (hh < h0 || hh >= h1) continue;
+      for (int cj = 0; cj < s.ow; ++cj) {
+        int w0, w1;
+        adaptive_window(cj, s.Wu, s.ow, w0, w1);
+        if (w < w0 || w >= w1) continue;
+        const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
+        const float *src = dPq + (long long)n * s.F + (ci * s.ow + cj) * s.A + av * V;
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e)
+      if (s.relu && !(u[e] > 0.f)) acc[e] = 0.f;
+    if constexpr (V == 4) {
+      *reinterpret_cast<float4 *>(dU + e0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+      dU[e0] = acc[0];
+    }
+    return;
+  }
+  b -= jb.nb_u;
+  if (b < jb.nb_t) {
     const long long total = (long long)s.A * R * S * K;
-    const long long i = (long long)(blockIdx.x - nb_main) * HT + threadIdx.x;
+    const long long i = (long long)b * HT + t;
     if (i >= total) return;
     const int a = (int)(i % s.A);
     long long r = i / s.A;
@@ -246,48 +309,7 @@ __global__ __launch_bounds__(HT) void pool_relu_bwd_kernel(HeadShape s, const fl
     WaT[i] = Wa[(((long long)a * R + (R - 1 - rr)) * S + (S - 1 - sx)) * K + k];
     return;
   }
-  const int AV = s.A / V;
-  const long long total = (long long)s.B * s.Hu * s.Wu * AV;
-  const long long i = (long long)blockIdx.x * HT + threadIdx.x;
-  if (i >= total) return;
-  const int av = (int)(i % AV);
-  long long r = i / AV;
-  const int w = (int)(r % s.Wu);
-  r /= s.Wu;
-  const int hh = (int)(r % s.Hu);
-  const int n = (int)(r / s.Hu);
-  const long long e0 = i * V;
-  float u[V], acc[V];
-  if constexpr (V == 4) {
-    const float4 t4 = *reinterpret_cast<const float4 *>(U + e0);
-    u[0] = t4.x, u[1] = t4.y, u[2] = t4.z, u[3] = t4.w;
-  } else {
-    u[0] = U[e0];
-  }
-#pragma unroll
-  for (int e = 0; e < V; ++e) acc[e] = 0.f;
-  for (int ci = 0; ci < s.oh; ++ci) {
-    int h0, h1;
-    adaptive_window(ci, s.Hu, s.oh, h0, h1);
-    if (hh < h0 || hh >= h1) continue;
-    for (int cj = 0; cj < s.ow; ++cj) {
-      int w0, w1;
-      adaptive_window(cj, s.Wu, s.ow, w0, w1);
-      if (w < w0 || w >= w1) continue;
-      const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
-      const float *src = dPq + (long long)n * s.F + (ci * s.ow + cj) * s.A + av * V;
-#pragma unroll
-      for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < V; ++e)
-    if (s.relu && !(u[e] > 0.f)) acc[e] = 0.f;
-  if constexpr (V == 4) {
-    *reinterpret_cast<float4 *>(dU + e0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-  } else {
-    dU[e0] = acc[0];
-  }
+  loss_mean_block(loss_n, s.B, loss_out, red);
 }
 
 }  // namespace
@@ -313,9 +335,9 @@ hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int
 }
 
 hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
-                          const float *bf, float *dz, float *loss_n, hipStream_t st) {
+                          const float *bf, float *dz, float *loss_n, float *dPq, hipStream_t st) {
   const size_t lds = (size_t)(h.F + h.Cls + 8) * sizeof(float);
-  hipLaunchKernelGGL(head_fc_kernel, dim3(h.B), dim3(HT), lds, st, h, Pq, labels, Wf, bf, dz, loss_n);
+  hipLaunchKernelGGL(head_fc_kernel, dim3(h.B), dim3(HT), lds, st, h, Pq, labels, Wf, bf, dz, loss_n, dPq);
   return hipGetLastError();
 }
 
@@ -324,30 +346,26 @@ hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, const float *Wf, float *dWf,
-                         float *dbf, float *dPq, hipStream_t st) {
-  int fch = 16;
-  while (fch < 64 && fch < h.F) fch *= 2;
-  const int nchunks = (h.F + fch - 1) / fch;
-  const int nb_w = h.Cls * nchunks;
-  const int nb_p = (int)(((long long)h.B * h.F + HT - 1) / HT);
-  hipLaunchKernelGGL(fc_bwd_kernel, dim3(nb_w + nb_p), dim3(HT), 0, st, h, Pq, dz, Wf, dWf, dbf, dPq, nb_w, fch,
-                     nchunks);
-  return hipGetLastError();
-}
-
-hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU, const float *Wa,
-                                float *WaT, int R, int S, int K, hipStream_t st) {
+hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,
+                           const float *U, const float *dPq, float *dU, const float *Wa, float *WaT, int R, int S,
+                           int K, const float *loss_n, float *loss_out, hipStream_t st) {
+  HeadBwdJobs jb;
+  // feature lanes per workgroup: few, so that many batch slices share the reduction over n
+  jb.fch = 8;
+  while (jb.fch < 32 && jb.fch * 2 <= h.F) jb.fch *= 2;
+  jb.nchunks = (h.F + jb.fch - 1) / jb.fch;
+  jb.nb_w = h.Cls * jb.nchunks;
   const int V = h.A % 4 == 0 ? 4 : 1;
   const long long total = (long long)h.B * h.Hu * h.Wu * (h.A / V);
-  const int nb_main = (int)((total + HT - 1) / HT);
-  const int nb_t = Wa ? (int)(((long long)h.A * R * S * K + HT - 1) / HT) : 0;
+  jb.nb_u = (int)((total + HT - 1) / HT);
+  jb.nb_t = Wa ? (int)(((long long)h.A * R * S * K + HT - 1) / HT) : 0;
+  const dim3 grid((unsigned)(jb.nb_w + jb.nb_u + jb.nb_t + (loss_out ? 1 : 0)));
   if (V == 4)
-    hipLaunchKernelGGL(pool_relu_bwd_kernel<4>, dim3(nb_main + nb_t), dim3(HT), 0, st, h, U, dPq, dU, nb_main, Wa, WaT,
-                       R, S, K);
+    hipLaunchKernelGGL(head_bwd_kernel<4>, grid, dim3(HT), 0, st, h, jb, Pq, dz, dWf, dbf, U, dPq, dU, Wa, WaT, R, S, K,
+                       loss_n, loss_out);
   else
-    hipLaunchKernelGGL(pool_relu_bwd_kernel<1>, dim3(nb_main + nb_t), dim3(HT), 0, st, h, U, dPq, dU, nb_main, Wa, WaT,
-                       R, S, K);
+    hipLaunchKernelGGL(head_bwd_kernel<1>, grid, dim3(HT), 0, st, h, jb, Pq, dz, dWf, dbf, U, dPq, dU, Wa, WaT, R, S, K,
+                       loss_n, loss_out);
   return hipGetLastError();
 }
 

@@ -246,6 +246,7 @@ HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
   return h;
 }
 
+// loss_out == nullptr: the batch mean is left to the backward launch that follows (run_bwd)
 int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const int32_t *labels,
                     const nf_aux_params *ap, float *loss_out, void *ws, const WsLayout &w, hipStream_t st) {
   FwdProblem f;
@@ -266,27 +267,26 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
   NF_RUN(st, "head_pool", 0.0, 4.0 * (u * (ks ? ks + 1.0 : 1.0) + (double)B * ad.F),
          launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.part), ks, ap->ba, wsf(ws, w.Pq), st));
-  NF_RUN(st, "head_fc", 2.0 * B * fc, 4.0 * ((double)B * fc + (double)B * (ad.F + a->n_classes)),
-         launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), st));
-  NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
+  NF_RUN(st, "head_fc", 4.0 * B * fc, 4.0 * (2.0 * B * fc + (double)B * (2.0 * ad.F + a->n_classes)),
+         launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), wsf(ws, w.dPq), st));
+  if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
   return NF_OK;
 }
 
 int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B,
                 const float *x, const float *xs, const float *y, const nf_layer_params *p,
-                const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga, void *ws,
-                const WsLayout &w, hipStream_t st) {
+                const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga, float *loss_out,
+                void *ws, const WsLayout &w, hipStream_t st) {
   (void)p;
   const bool pooled = d->pool_kind != 0;
   const HeadShape hs = head_shape(a, ad, B);
   float *dU = wsf(ws, w.dU), *dZ = wsf(ws, w.T_dZ);
-  // gamma_n, then back through F_n and the aux ReLU
+  // gamma_n weight gradient, back through F_n and the aux ReLU (dPq came with the forward)
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
-  NF_RUN(st, "fc_bwd", 4.0 * B * fc, 4.0 * (2.0 * fc + (double)B * (2.0 * ad.F + a->n_classes)),
-         launch_fc_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ap->Wf, ga->Wf, ga->bf, wsf(ws, w.dPq), st));
   const double wa = (double)a->A * a->R * a->S * a->C_in;
-  NF_RUN(st, "pool_relu_bwd", 0.0, 4.0 * (2.0 * u + (double)B * ad.F) + 8.0 * wa,
-         launch_pool_relu_bwd(hs, wsf(ws, w.U), wsf(ws, w.dPq), dU, ap->Wa, wsf(ws, w.WaT), a->R, a->S, a->C_in, st));
+  NF_RUN(st, "head_bwd", 2.0 * B * fc, 4.0 * (fc + (double)B * (2.0 * ad.F + a->n_classes) + 2.0 * u) + 8.0 * wa,
+         launch_head_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ga->Wf, ga->bf, wsf(ws, w.U), wsf(ws, w.dPq), dU, ap->Wa,
+                         wsf(ws, w.WaT), a->R, a->S, a->C_in, wsf(ws, w.loss_n), loss_out, st));
   // beta_n: weight + bias gradient
   {
     WgradProblem g;
@@ -520,7 +520,7 @@ int32_t nf_local_bwd_wgrad(const nf_layer_desc *d, const nf_aux_desc *a, int32_t
   if (!aligned16(y)) return NF_ERR_BAD_DESC;
   const WsLayout w = ws_layout(d, ld, a, ad, B);
   if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
-  return run_bwd(d, ld, a, ad, B, x, x_skip, y, p, ap, gp, ga, ws, w, static_cast<hipStream_t>(stream));
+  return run_bwd(d, ld, a, ad, B, x, x_skip, y, p, ap, gp, ga, nullptr, ws, w, static_cast<hipStream_t>(stream));
 }
 
 int32_t nf_sgd_update(const nf_sgd_desc *s, int32_t n_tensors, float *const *w, const float *const *g,
@@ -599,8 +599,9 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
   // Algorithm 2: forward with the current weights (this y_out is what the next layer reads),
   // head + loss, local gradients, update.
   if ((rc = run_layer_fwd(d, ld, B, x, x_skip, p, y_out, ws, w, st))) return rc;
-  if ((rc = run_aux_fwd(a, ad, B, y_out, labels, ap, loss_out, ws, w, st))) return rc;
-  if ((rc = run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, ws, w, st))) return rc;
+  // the batch-mean loss rides on the head's backward launch
+  if ((rc = run_aux_fwd(a, ad, B, y_out, labels, ap, nullptr, ws, w, st))) return rc;
+  if ((rc = run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, loss_out, ws, w, st))) return rc;
   SgdTensors t;
   std::memset(&t, 0, sizeof(t));
   t.n = collect_sgd(d, a, ad, p, ap, gp, ga, s->momentum != 0.f ? vp : nullptr, s->momentum != 0.f ? va : nullptr, &t);

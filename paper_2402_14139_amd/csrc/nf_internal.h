@@ -79,17 +79,17 @@ struct HeadShape {
 // part[splits][B*Hu*Wu*A] of the aux convolution: U = act(sum_z part[z] + ba) (written out).
 hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
                             hipStream_t st);
+// logits, softmax cross-entropy, dz, per-sample losses and dPq = dz * Wf
 hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
-                          const float *bf, float *dz, float *loss_n, hipStream_t st);
+                          const float *bf, float *dz, float *loss_n, float *dPq, hipStream_t st);
 hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStream_t st);
-hipError_t launch_fc_bwd(const HeadShape &h, const float *Pq, const float *dz, const float *Wf, float *dWf,
-                         float *dbf, float *dPq, hipStream_t st);
-// also writes WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa is given
-hipError_t launch_pool_relu_bwd(const HeadShape &h, const float *U, const float *dPq, float *dU, const float *Wa,
-                                float *WaT, int R, int S, int K, hipStream_t st);
+// one launch: dWf, dbf; dU (pool + aux ReLU backward); WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa
+// is given; the batch-mean loss when loss_out is given
+hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,
+                           const float *U, const float *dPq, float *dU, const float *Wa, float *WaT, int R, int S,
+                           int K, const float *loss_n, float *loss_out, hipStream_t st);
 
 // ---- elementwise / data movement ----
-hipError_t launch_flip_transpose(const float *Wa, float *WaT, int A, int R, int S, int K, hipStream_t st);
 hipError_t launch_maxpool_fwd(const float *T, float *Y, uint8_t *arg, int B, int Ho, int Wo, int K, int Hp,
                               int Wp, int pk, int ps, int pp, hipStream_t st);
 hipError_t launch_maxpool_bwd(const float *dY, const float *Y, const uint8_t *arg, float *dZ, int B, int Ho,
