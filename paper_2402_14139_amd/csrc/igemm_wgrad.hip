@@ -263,62 +263,96 @@ __global__ __launch_bounds__(NTHREADS) void igemm_wgrad_kernel(WgradProblem p) {
   }
 }
 
-// Sum of the split partials in a fixed order.  A workgroup owns 256/ZS groups of four
-// consecutive elements of the flattened [P][Qld] tile array; its ZS thread rows each add every
-// ZS-th split with 16-byte loads, then the ZS row sums are added in order through LDS.  The
-// workgroups past `main_blocks` do the same for the bias partials.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part,
-                                                           const float *__restrict__ part_b, int splits, int P, int Q,
-                                                           int Qld, int Q0, float *__restrict__ out0,
-                                                           float *__restrict__ out1, float *__restrict__ ob, int ZS,
-                                                           int main_blocks) {
+// Sum of the split partials in a fixed order, for up to two weight gradients in one launch,
+// optionally followed in place by the update line of Algorithm 2 (momentum SGD) for the tensors
+// just reduced and for up to two more whose gradient is already final.
+// Per gradient: a workgroup owns 256/ZS groups of four consecutive elements of the flattened
+// [P][Qld] tile array; its ZS thread rows each add every ZS-th split with 16-byte loads, then the
+// ZS row sums are added in order through LDS.  Further workgroups do the same for the bias
+// partials (16 columns x 16 thread rows each).
+__device__ inline void sgd_elem(float g, float *w, float *v, long long i, float lr, float mu) {
+  if (!w) return;
+  if (v && mu != 0.f) {
+    g = mu * v[i] + g;
+    v[i] = g;
+  }
+  w[i] -= lr * g;
+}
+
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(ReduceSgd r) {
   __shared__ float4 red[256];
   const int t = threadIdx.x;
-  const int cols = 256 / ZS;
-  const int col = t % cols, zs = t / cols;
-  if ((int)blockIdx.x < main_blocks) {
-    const long long n4 = ((long long)P * Qld) >> 2;  // Qld is a multiple of 4
-    const long long i4 = (long long)blockIdx.x * cols + col;
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i4 < n4) {
-      const float4 *src = reinterpret_cast<const float4 *>(part) + i4;
-      for (int z = zs; z < splits; z += ZS) {
-        const float4 v = src[(long long)z * n4];
-        s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
-      }
-    }
-    red[t] = s;
-    __syncthreads();
-    if (zs == 0 && i4 < n4) {
-      for (int k = 1; k < ZS; ++k) {
-        const float4 v = red[k * cols + col];
-        s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
-      }
-      const long long e = i4 << 2;
-      const int pr = (int)(e / Qld), q = (int)(e - (long long)pr * Qld);
-      const float vals[4] = {s.x, s.y, s.z, s.w};
+  int b = blockIdx.x;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int qq = q + k;
-        if (qq < Q0)
-          out0[(long long)pr * Q0 + qq] = vals[k];
-        else if (qq < Q)
-          out1[(long long)pr * (Q - Q0) + (qq - Q0)] = vals[k];
+  for (int ji = 0; ji < 2; ++ji) {
+    if (ji >= r.njobs) break;
+    const WgradReduce &jb = r.job[ji];
+    if (b < jb.main_blocks) {
+      const int ZS = jb.ZS, cols = 256 / ZS;
+      const int col = t % cols, zs = t / cols;
+      const long long n4 = ((long long)jb.P * jb.Qld) >> 2;  // Qld is a multiple of 4
+      const long long i4 = (long long)b * cols + col;
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i4 < n4) {
+        const float4 *src = reinterpret_cast<const float4 *>(jb.part) + i4;
+        for (int z = zs; z < jb.splits; z += ZS) {
+          const float4 v = src[(long long)z * n4];
+          s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+        }
       }
+      red[t] = s;
+      __syncthreads();
+      if (zs == 0 && i4 < n4) {
+        for (int k = 1; k < ZS; ++k) {
+          const float4 v = red[k * cols + col];
+          s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+        }
+        const long long e = i4 << 2;
+        const int pr = (int)(e / jb.Qld), q = (int)(e - (long long)pr * jb.Qld);
+        const float vals[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int qq = q + k;
+          if (qq < jb.Q0) {
+            const long long o = (long long)pr * jb.Q0 + qq;
+            jb.out0[o] = vals[k];
+            sgd_elem(vals[k], jb.w0, jb.v0, o, r.lr, r.mu);
+          } else if (qq < jb.Q) {
+            const long long o = (long long)pr * (jb.Q - jb.Q0) + (qq - jb.Q0);
+            jb.out1[o] = vals[k];
+            sgd_elem(vals[k], jb.w1, jb.v1, o, r.lr, r.mu);
+          }
+        }
+      }
+      return;
     }
-  } else if (ob) {
-    // bias partials: each extra workgroup owns 16 columns, 16 thread rows add every 16th split
-    const int pr = ((int)blockIdx.x - main_blocks) * 16 + (t & 15), zb = t >> 4;
-    float sb = 0.f;
-    if (pr < P)
-      for (int z = zb; z < splits; z += 16) sb += part_b[(long long)z * P + pr];
-    float *redb = reinterpret_cast<float *>(red);
-    redb[t] = sb;
-    __syncthreads();
-    if (zb == 0 && pr < P) {
-      for (int k = 1; k < 16; ++k) sb += redb[k * 16 + (t & 15)];
-      ob[pr] = sb;
+    b -= jb.main_blocks;
+    if (b < jb.bias_blocks) {
+      const int pr = b * 16 + (t & 15), zb = t >> 4;
+      float sb = 0.f;
+      if (pr < jb.P)
+        for (int z = zb; z < jb.splits; z += 16) sb += jb.part_b[(long long)z * jb.P + pr];
+      float *redb = reinterpret_cast<float *>(red);
+      redb[t] = sb;
+      __syncthreads();
+      if (zb == 0 && pr < jb.P) {
+        for (int k = 1; k < 16; ++k) sb += redb[k * 16 + (t & 15)];
+        jb.ob[pr] = sb;
+        sgd_elem(sb, jb.wb, jb.vb, pr, r.lr, r.mu);
+      }
+      return;
     }
+    b -= jb.bias_blocks;
+  }
+#pragma unroll
+  for (int xi = 0; xi < 2; ++xi) {
+    if (xi >= r.nx) break;
+    if (b < r.xblocks[xi]) {
+      const long long i = (long long)b * 256 + t;
+      if (i < r.xn[xi]) sgd_elem(r.xg[xi][i], r.xw[xi], r.xv[xi], i, r.lr, r.mu);
+      return;
+    }
+    b -= r.xblocks[xi];
   }
 }
 
@@ -386,15 +420,26 @@ hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char 
   return launch_cfg<32, 256, 1, 4>(p, vec, st);
 }
 
-hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int splits, int P, int Q, int Qld,
-                               int Q0, float *out0, float *out1, float *ob, hipStream_t st) {
-  int ZS = 1;
-  while (ZS < 16 && ZS < splits) ZS *= 2;
-  const int cols = 256 / ZS;
-  const long long n4 = ((long long)P * Qld) / 4;
-  const int main_blocks = (int)((n4 + cols - 1) / cols);
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)(main_blocks + (ob ? (P + 15) / 16 : 0))), dim3(256), 0, st, part, part_b,
-                     splits, P, Q, Qld, Q0, out0, out1, ob, ZS, main_blocks);
+hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r0, hipStream_t st) {
+  ReduceSgd r = r0;
+  unsigned blocks = 0;
+  for (int j = 0; j < r.njobs; ++j) {
+    WgradReduce &jb = r.job[j];
+    int ZS = 1;
+    while (ZS < 16 && ZS < jb.splits) ZS *= 2;
+    const int cols = 256 / ZS;
+    const long long n4 = ((long long)jb.P * jb.Qld) / 4;
+    jb.ZS = ZS;
+    jb.main_blocks = (int)((n4 + cols - 1) / cols);
+    jb.bias_blocks = jb.ob ? (jb.P + 15) / 16 : 0;
+    blocks += (unsigned)(jb.main_blocks + jb.bias_blocks);
+  }
+  for (int x = 0; x < r.nx; ++x) {
+    r.xblocks[x] = (int)((r.xn[x] + 255) / 256);
+    blocks += (unsigned)r.xblocks[x];
+  }
+  if (!blocks) return hipSuccess;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(256), 0, st, r);
   return hipGetLastError();
 }
 

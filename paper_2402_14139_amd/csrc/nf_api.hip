@@ -85,7 +85,7 @@ int32_t check_sizes(const nf_layer_desc *d, const LayerDims &ld, int32_t B) {
 }
 
 struct WsLayout {
-  size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, total;
+  size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
   int ksplits_aux;  // reduction splits of the aux convolution forward (partials alias `part`)
 };
@@ -120,14 +120,14 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     w.Qld_layer = (Ql + 3) / 4 * 4;
     w.splits_aux = wgrad_pick_splits(a->A, Qa, B * ad.Hu * ad.Wu);
     w.splits_layer = wgrad_pick_splits(d->C_out, Ql, B * ld.Ho * ld.Wo);
+    // split partials of the two weight gradients live side by side: one launch reduces both
     const size_t pa = (size_t)w.splits_aux * a->A * w.Qld_aux, pl = (size_t)w.splits_layer * d->C_out * w.Qld_layer;
     w.ksplits_aux = igemm_fwd_pick_ksplits(B * ad.Hu * ad.Wu, a->A, Qa, a->C_in, a->R * a->S);
-    const size_t pk = w.ksplits_aux > 1 ? (size_t)w.ksplits_aux * u : 0;
-    size_t pmax = pa > pl ? pa : pl;
-    if (pk > pmax) pmax = pk;
-    w.part = take(pmax * f);
-    const size_t ba = (size_t)w.splits_aux * a->A, bl = (size_t)w.splits_layer * d->C_out;
-    w.part_b = take((ba > bl ? ba : bl) * f);
+    const size_t pk = w.ksplits_aux > 1 ? (size_t)w.ksplits_aux * u : 0;  // aux forward partials: dead before the backward
+    w.part = take((pl > pk ? pl : pk) * f);
+    w.part_b = take((size_t)w.splits_layer * d->C_out * f);
+    w.part_aux = take(pa * f);
+    w.part_b_aux = take((size_t)w.splits_aux * a->A * f);
   }
   w.total = off ? off : ALIGN;
   return w;
@@ -197,21 +197,24 @@ int32_t enqueue_fwd(const FwdProblem &f, hipStream_t st) {
   return NF_OK;
 }
 
-int32_t enqueue_wgrad(const WgradProblem &g, float *out0, float *out1, float *ob, hipStream_t st) {
+int32_t enqueue_wgrad(const WgradProblem &g, hipStream_t st) {
   const double B = (double)g.M / ((double)g.Ho * g.Wo);
   const double flops = 2.0 * g.M * g.P * g.Q;
   double elems = (double)g.M * g.P + B * g.H * g.W * g.C + (double)g.P * g.Q;
   if (g.Cs) elems += B * g.Hs * g.Ws * g.Cs;
-  {
-    ProfScope sc(st);
-    const char *kn = "igemm_wgrad";
-    NF_HIP(launch_igemm_wgrad(g, st, &kn));
-    sc.done(kn, flops, 4.0 * elems);
-  }
-  const double red = ((double)g.splits + 1.0) * g.P * (g.Q + 1.0);
-  NF_RUN(st, "wgrad_reduce", 0.0, 4.0 * red,
-         launch_wgrad_reduce(g.part, g.part_b, g.splits, g.P, g.Q, g.Qld, g.RSC, out0, out1, ob, st));
+  ProfScope sc(st);
+  const char *kn = "igemm_wgrad";
+  NF_HIP(launch_igemm_wgrad(g, st, &kn));
+  sc.done(kn, flops, 4.0 * elems);
   return NF_OK;
+}
+
+WgradReduce reduce_job(const WgradProblem &g, float *out0, float *out1, float *ob) {
+  WgradReduce j;
+  std::memset((void *)&j, 0, sizeof(j));
+  j.part = g.part, j.part_b = g.part_b, j.splits = g.splits, j.P = g.P, j.Q = g.Q, j.Qld = g.Qld, j.Q0 = g.RSC;
+  j.out0 = out0, j.out1 = out1, j.ob = ob;
+  return j;
 }
 
 int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const float *x, const float *xs,
@@ -276,8 +279,12 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
 int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B,
                 const float *x, const float *xs, const float *y, const nf_layer_params *p,
                 const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga, float *loss_out,
-                void *ws, const WsLayout &w, hipStream_t st) {
-  (void)p;
+                const nf_sgd_desc *sgd, const nf_layer_params *vp, const nf_aux_params *va, void *ws,
+                const WsLayout &w, hipStream_t st) {
+  // sgd != nullptr: the update line of Algorithm 2 is applied by the launch that finishes the
+  // gradients (nothing reads the parameters after the data gradient)
+  ReduceSgd red;
+  std::memset((void *)&red, 0, sizeof(red));
   const bool pooled = d->pool_kind != 0;
   const HeadShape hs = head_shape(a, ad, B);
   float *dU = wsf(ws, w.dU), *dZ = wsf(ws, w.T_dZ);
@@ -291,15 +298,16 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
   {
     WgradProblem g;
     std::memset((void *)&g, 0, sizeof(g));
-    g.d = dU, g.x = y, g.part = wsf(ws, w.part), g.part_b = wsf(ws, w.part_b);
+    g.d = dU, g.x = y, g.part = wsf(ws, w.part_aux), g.part_b = wsf(ws, w.part_b_aux);
     g.H = a->H_in, g.W = a->W_in, g.C = a->C_in, g.R = a->R, g.S = a->S, g.stride = 1, g.pad = a->pad, g.Ho = ad.Hu,
     g.Wo = ad.Wu;
     g.P = a->A, g.M = B * ad.Hu * ad.Wu, g.RSC = a->R * a->S * a->C_in, g.Q = g.RSC, g.Qld = w.Qld_aux;
     g.splits = w.splits_aux;
     g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
     g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);
-    const int32_t rc = enqueue_wgrad(g, ga->Wa, nullptr, ga->ba, st);
+    const int32_t rc = enqueue_wgrad(g, st);
     if (rc) return rc;
+    red.job[1] = reduce_job(g, ga->Wa, nullptr, ga->ba);
   }
   // beta_n: data gradient w.r.t. the emitted activation, layer ReLU mask fused when un-pooled
   {
@@ -333,9 +341,30 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     g.splits = w.splits_layer;
     g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
     g.div_howo = FastDiv(ld.Ho * ld.Wo), g.div_wo = FastDiv(ld.Wo);
-    const int32_t rc = enqueue_wgrad(g, gp->W, gp->Wp, gp->b, st);
+    const int32_t rc = enqueue_wgrad(g, st);
     if (rc) return rc;
+    red.job[0] = reduce_job(g, gp->W, gp->Wp, gp->b);
   }
+  red.njobs = 2;
+  double nred = 0, nsgd = 0;
+  for (int j = 0; j < 2; ++j) nred += ((double)red.job[j].splits + 1.0) * red.job[j].P * (red.job[j].Q + 1.0);
+  if (sgd) {
+    const bool mom = sgd->momentum != 0.f;
+    red.lr = sgd->lr, red.mu = sgd->momentum;
+    red.job[0].w0 = p->W, red.job[0].w1 = p->Wp, red.job[0].wb = p->b;
+    red.job[1].w0 = ap->Wa, red.job[1].wb = ap->ba;
+    if (mom) {
+      red.job[0].v0 = vp->W, red.job[0].v1 = vp->Wp, red.job[0].vb = vp->b;
+      red.job[1].v0 = va->Wa, red.job[1].vb = va->ba;
+    }
+    red.nx = 2;
+    red.xw[0] = ap->Wf, red.xg[0] = ga->Wf, red.xv[0] = mom ? va->Wf : nullptr, red.xn[0] = (long long)a->n_classes * ad.F;
+    red.xw[1] = ap->bf, red.xg[1] = ga->bf, red.xv[1] = mom ? va->bf : nullptr, red.xn[1] = a->n_classes;
+    for (int j = 0; j < 2; ++j) nsgd += (double)red.job[j].P * (red.job[j].Q + 1.0);
+    nsgd += (double)red.xn[0] + (double)red.xn[1];
+    nsgd *= mom ? 16.0 : 8.0;  // bytes beyond the gradient write
+  }
+  NF_RUN(st, sgd ? "wgrad_reduce_sgd" : "wgrad_reduce", 0.0, 4.0 * nred + nsgd, launch_wgrad_reduce_sgd(red, st));
   return NF_OK;
 }
 
@@ -374,24 +403,6 @@ int32_t check_aux_ptrs(const nf_aux_params *ap) {
 int32_t check_pair(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a) {
   if (a->C_in != d->C_out || a->H_in != ld.Hp || a->W_in != ld.Wp) return NF_ERR_BAD_DESC;
   return NF_OK;
-}
-
-int collect_sgd(const nf_layer_desc *d, const nf_aux_desc *a, const AuxDims &ad, const nf_layer_params *p,
-                const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga,
-                const nf_layer_params *vp, const nf_aux_params *va, SgdTensors *t) {
-  int n = 0;
-  auto add = [&](float *w, const float *g, float *v, long long numel) {
-    t->w[n] = w, t->g[n] = g, t->v[n] = v, t->numel[n] = numel;
-    ++n;
-  };
-  add(p->W, gp->W, vp ? vp->W : nullptr, (long long)d->C_out * d->R * d->S * d->C_in);
-  add(p->b, gp->b, vp ? vp->b : nullptr, d->C_out);
-  if (d->skip_kind == 2) add(p->Wp, gp->Wp, vp ? vp->Wp : nullptr, (long long)d->C_out * d->skip_C);
-  add(ap->Wa, ga->Wa, va ? va->Wa : nullptr, (long long)a->A * a->R * a->S * a->C_in);
-  add(ap->ba, ga->ba, va ? va->ba : nullptr, a->A);
-  add(ap->Wf, ga->Wf, va ? va->Wf : nullptr, (long long)a->n_classes * ad.F);
-  add(ap->bf, ga->bf, va ? va->bf : nullptr, a->n_classes);
-  return n;
 }
 
 }  // namespace
@@ -520,7 +531,8 @@ int32_t nf_local_bwd_wgrad(const nf_layer_desc *d, const nf_aux_desc *a, int32_t
   if (!aligned16(y)) return NF_ERR_BAD_DESC;
   const WsLayout w = ws_layout(d, ld, a, ad, B);
   if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
-  return run_bwd(d, ld, a, ad, B, x, x_skip, y, p, ap, gp, ga, nullptr, ws, w, static_cast<hipStream_t>(stream));
+  return run_bwd(d, ld, a, ad, B, x, x_skip, y, p, ap, gp, ga, nullptr, nullptr, nullptr, nullptr, ws, w,
+                 static_cast<hipStream_t>(stream));
 }
 
 int32_t nf_sgd_update(const nf_sgd_desc *s, int32_t n_tensors, float *const *w, const float *const *g,
@@ -601,12 +613,8 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
   if ((rc = run_layer_fwd(d, ld, B, x, x_skip, p, y_out, ws, w, st))) return rc;
   // the batch-mean loss rides on the head's backward launch
   if ((rc = run_aux_fwd(a, ad, B, y_out, labels, ap, nullptr, ws, w, st))) return rc;
-  if ((rc = run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, loss_out, ws, w, st))) return rc;
-  SgdTensors t;
-  std::memset(&t, 0, sizeof(t));
-  t.n = collect_sgd(d, a, ad, p, ap, gp, ga, s->momentum != 0.f ? vp : nullptr, s->momentum != 0.f ? va : nullptr, &t);
-  t.lr = s->lr, t.mu = s->momentum;
-  return enqueue_sgd(t, st);
+  // ... and the update on the launch that finishes the weight gradients
+  return run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, loss_out, s, vp, va, ws, w, st);
 }
 
 int32_t nf_prof_begin(void) {

@@ -66,10 +66,29 @@ hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char 
 // software-pipelined buffer-load variant (igemm_wgrad_fast.hip); launch_igemm_wgrad picks it when applicable
 bool igemm_wgrad_fast_applicable(const WgradProblem &p);
 hipError_t launch_igemm_wgrad_fast(const WgradProblem &p, hipStream_t st, const char **kernel);
-// out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length Q-Q0) = sum_z part[z][p][q];
-// ob[p] = sum_z part_b[z][p]
-hipError_t launch_wgrad_reduce(const float *part, const float *part_b, int splits, int P, int Q, int Qld,
-                               int Q0, float *out0, float *out1, float *ob, hipStream_t st);
+// One weight gradient to finish: out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length
+// Q-Q0) = sum_z part[z][p][q]; ob[p] = sum_z part_b[z][p].  w*/v* (may be null): parameters and
+// momentum buffers updated in place right after, same layout as out0/out1/ob.
+struct WgradReduce {
+  const float *part, *part_b;
+  int splits, P, Q, Qld, Q0;
+  float *out0, *out1, *ob;
+  float *w0, *w1, *wb, *v0, *v1, *vb;
+  int ZS, main_blocks, bias_blocks;  // filled by the launcher
+};
+struct ReduceSgd {
+  WgradReduce job[2];
+  int njobs;
+  // tensors whose gradient is final already (update only; used when lr/mu are given)
+  float *xw[2];
+  const float *xg[2];
+  float *xv[2];
+  long long xn[2];
+  int xblocks[2];  // filled by the launcher
+  int nx;
+  float lr, mu;
+};
+hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r, hipStream_t st);
 
 // ---- head (Eq. 2 after the aux conv, Eq. 3) ----
 struct HeadShape {
