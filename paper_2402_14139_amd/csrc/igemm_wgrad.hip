@@ -309,6 +309,24 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(ReduceSgd r) {
         }
         const long long e = i4 << 2;
         const int pr = (int)(e / jb.Qld), q = (int)(e - (long long)pr * jb.Qld);
+        if (jb.vec4) {  // no group of four straddles a row end or the out0/out1 boundary
+          const bool first = q < jb.Q0;
+          const long long o = first ? (long long)pr * jb.Q0 + q : (long long)pr * (jb.Q - jb.Q0) + (q - jb.Q0);
+          float *out = first ? jb.out0 : jb.out1, *w = first ? jb.w0 : jb.w1, *v = first ? jb.v0 : jb.v1;
+          *reinterpret_cast<float4 *>(out + o) = s;
+          if (w) {
+            float4 g = s;
+            if (v && r.mu != 0.f) {
+              const float4 vv = *reinterpret_cast<const float4 *>(v + o);
+              g.x = r.mu * vv.x + g.x, g.y = r.mu * vv.y + g.y, g.z = r.mu * vv.z + g.z, g.w = r.mu * vv.w + g.w;
+              *reinterpret_cast<float4 *>(v + o) = g;
+            }
+            float4 wv = *reinterpret_cast<const float4 *>(w + o);
+            wv.x -= r.lr * g.x, wv.y -= r.lr * g.y, wv.z -= r.lr * g.z, wv.w -= r.lr * g.w;
+            *reinterpret_cast<float4 *>(w + o) = wv;
+          }
+          return;
+        }
         const float vals[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -430,6 +448,11 @@ hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r0, hipStream_t st) {
     const int cols = 256 / ZS;
     const long long n4 = ((long long)jb.P * jb.Qld) / 4;
     jb.ZS = ZS;
+    auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+    jb.vec4 = (jb.Q0 % 4 == 0 && jb.Q % 4 == 0 && jb.Qld == jb.Q && al16(jb.out0) && al16(jb.out1) && al16(jb.w0) &&
+               al16(jb.w1) && al16(jb.v0) && al16(jb.v1))
+                  ? 1
+                  : 0;
     jb.main_blocks = (int)((n4 + cols - 1) / cols);
     jb.bias_blocks = jb.ob ? (jb.P + 15) / 16 : 0;
     blocks += (unsigned)(jb.main_blocks + jb.bias_blocks);
