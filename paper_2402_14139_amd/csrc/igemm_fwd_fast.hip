@@ -59,8 +59,12 @@ struct Mfma<16> {
 
 // BK = reduction length staged per step (one barrier per step): 32 for the wide tiles, longer for
 // the skinny ones, whose steps are dominated by the fixed cost of the barrier.
-template <int BM, int BN, int BK, int WM, int WN, int MF, bool PROJ, bool SCHED>
+// MODE 0: plain; 1: projection shortcut appended to the reduction; 2: the epilogue operand (identity
+// shortcut or ReLU mask, one value per output element) is fetched into registers before the main
+// loop instead of at its end, where nothing would hide the latency.
+template <int BM, int BN, int BK, int WM, int WN, int MF, int MODE, bool SCHED>
 __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem p, FastAux q) {
+  constexpr bool PROJ = MODE == 1, EPI = MODE == 2;
   using MM = Mfma<MF>;
   using acc_t = typename MM::acc_t;
   constexpr int LDK = BK + 4;        // +4 floats: 16-byte row reads of consecutive rows hit distinct banks
@@ -256,6 +260,21 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   };
 
   gload(kb0, 0);
+  float epi[EPI ? MT : 1][EPI ? NT : 1][EPI ? MM::NACC : 1];
+  if constexpr (EPI) {
+    const float *src = p.addsrc ? p.addsrc : p.mask;
+#pragma unroll
+    for (int b = 0; b < NT; ++b) {
+      const int n = n0 + wn * TN + b * MF + j;
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int e = 0; e < MM::NACC; ++e) {
+          const int m = m0 + wm * TM + a * MF + MM::row(e, g);
+          epi[a][b][e] = (n < p.N && m < p.M) ? src[(long long)m * p.N + n] : 0.f;
+        }
+    }
+  }
   lstore(0, 0);
   gload(kb0 + 1, 1);
   __syncthreads();
@@ -300,9 +319,9 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
         if (m >= p.M) continue;
         const long long o = (long long)m * p.N + n;
         float v = acc[a][b][e] + bias;
-        if (p.addsrc) v += p.addsrc[o];
+        if (p.addsrc) v += EPI ? epi[EPI ? a : 0][EPI ? b : 0][EPI ? e : 0] : p.addsrc[o];
         if (p.relu) v = v > 0.f ? v : 0.f;
-        if (p.mask) v = p.mask[o] > 0.f ? v : 0.f;
+        if (p.mask) v = (EPI ? epi[EPI ? a : 0][EPI ? b : 0][EPI ? e : 0] : p.mask[o]) > 0.f ? v : 0.f;
         p.out[o] = v;
       }
     }
@@ -319,10 +338,14 @@ hipError_t launch_cfg(const FwdProblem &p, FastAux q, hipStream_t st) {
   const int splits = p.ksplits > 1 ? p.ksplits : 1;
   q.kb_per = (nkb + splits - 1) / splits;
   const dim3 grid((unsigned)tiles, (unsigned)splits);
+  // exactly one of addsrc / mask, no projection, no split: prefetch it (MODE 2)
+  const bool epi = !q.nkb_proj && splits == 1 && ((p.addsrc != nullptr) != (p.mask != nullptr));
   if (q.nkb_proj)
-    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, true, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, 1, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
+  else if (epi)
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, 2, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
   else
-    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, false, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
+    hipLaunchKernelGGL((igemm_fwd_fast_kernel<BM, BN, BK, WM, WN, MF, 0, SCHED>), grid, dim3(WM * WN * 64), 0, st, p, q);
   return hipGetLastError();
 }
 
