@@ -84,6 +84,17 @@ int32_t check_sizes(const nf_layer_desc *d, const LayerDims &ld, int32_t B) {
   return NF_OK;
 }
 
+// shape part of the aux convolution's weight-gradient problem (pointers and splits left to the caller)
+WgradProblem aux_wgrad_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
+  WgradProblem g;
+  std::memset((void *)&g, 0, sizeof(g));
+  g.H = a->H_in, g.W = a->W_in, g.C = a->C_in, g.R = a->R, g.S = a->S, g.stride = 1, g.pad = a->pad, g.Ho = ad.Hu,
+  g.Wo = ad.Wu;
+  g.P = a->A, g.M = B * ad.Hu * ad.Wu, g.RSC = a->R * a->S * a->C_in, g.Q = g.RSC;
+  g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);
+  return g;
+}
+
 struct WsLayout {
   size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
@@ -118,7 +129,9 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     const int Qa = a->R * a->S * a->C_in, Ql = d->R * d->S * d->C_in + (d->skip_kind == 2 ? d->skip_C : 0);
     w.Qld_aux = (Qa + 3) / 4 * 4;
     w.Qld_layer = (Ql + 3) / 4 * 4;
-    w.splits_aux = wgrad_pick_splits(a->A, Qa, B * ad.Hu * ad.Wu);
+    w.splits_aux = igemm_wgrad_small_applicable(aux_wgrad_shape(a, ad, B))
+                       ? igemm_wgrad_small_splits(a->A, a->C_in, B, a->H_in)
+                       : wgrad_pick_splits(a->A, Qa, B * ad.Hu * ad.Wu);
     w.splits_layer = wgrad_pick_splits(d->C_out, Ql, B * ld.Ho * ld.Wo);
     // split partials of the two weight gradients live side by side: one launch reduces both
     const size_t pa = (size_t)w.splits_aux * a->A * w.Qld_aux, pl = (size_t)w.splits_layer * d->C_out * w.Qld_layer;
@@ -296,12 +309,9 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
                          wsf(ws, w.WaT), a->R, a->S, a->C_in, wsf(ws, w.loss_n), loss_out, st));
   // beta_n: weight + bias gradient
   {
-    WgradProblem g;
-    std::memset((void *)&g, 0, sizeof(g));
+    WgradProblem g = aux_wgrad_shape(a, ad, B);
     g.d = dU, g.x = y, g.part = wsf(ws, w.part_aux), g.part_b = wsf(ws, w.part_b_aux);
-    g.H = a->H_in, g.W = a->W_in, g.C = a->C_in, g.R = a->R, g.S = a->S, g.stride = 1, g.pad = a->pad, g.Ho = ad.Hu,
-    g.Wo = ad.Wu;
-    g.P = a->A, g.M = B * ad.Hu * ad.Wu, g.RSC = a->R * a->S * a->C_in, g.Q = g.RSC, g.Qld = w.Qld_aux;
+    g.Qld = w.Qld_aux;
     g.splits = w.splits_aux;
     g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
     g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);

@@ -66,6 +66,11 @@ hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char 
 // software-pipelined buffer-load variant (igemm_wgrad_fast.hip); launch_igemm_wgrad picks it when applicable
 bool igemm_wgrad_fast_applicable(const WgradProblem &p);
 hipError_t launch_igemm_wgrad_fast(const WgradProblem &p, hipStream_t st, const char **kernel);
+// 3x3 / stride 1 / pad 1 with at most 32 output channels (igemm_wgrad_small.hip): 4x4x1 MFMA with a
+// sliding register window; `splits` are ranges of image rows there (any count is valid)
+bool igemm_wgrad_small_applicable(const WgradProblem &p);
+int igemm_wgrad_small_splits(int P, int C, int B, int H);
+hipError_t launch_igemm_wgrad_small(const WgradProblem &p, hipStream_t st, const char **kernel);
 // One weight gradient to finish: out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length
 // Q-Q0) = sum_z part[z][p][q]; ob[p] = sum_z part_b[z][p].  w*/v* (may be null): parameters and
 // momentum buffers updated in place right after, same layout as out0/out1/ob.
