@@ -79,7 +79,7 @@ struct WgradReduce {
   int splits, P, Q, Qld, Q0;
   float *out0, *out1, *ob;
   float *w0, *w1, *wb, *v0, *v1, *vb;
-  int ZS, main_blocks, bias_blocks, vec4;  // filled by the launcher
+  int ZS, main_blocks, bias_blocks, vec4, direct;  // filled by the launcher
 };
 struct ReduceSgd {
   WgradReduce job[2];
