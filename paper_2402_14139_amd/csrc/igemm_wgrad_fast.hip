@@ -73,8 +73,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   const int lane = t & 63, wave = t >> 6;
   const int wp = wave / WQ, wq = wave % WQ;
   const int j = lane & 31, h = lane >> 5;
-  const int p0 = blockIdx.y * BP, q0 = blockIdx.x * BQ;
-  const int m_begin = blockIdx.z * p.m_per_split;
+  // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by linear index.  The
+  // index is re-mapped so that each XCD gets a contiguous run of (split, p-tile, q-tile) with the
+  // tiles fastest: all tiles of one split read the same rows of D and X, which then come from that
+  // XCD's L2 once instead of from every L2.
+  const int gx = gridDim.x, gy = gridDim.y;
+  const int nwg = gx * gy * (int)gridDim.z;
+  const int lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  const int per = nwg >> 3, rem = nwg & 7, xcd = lin & 7, slot = lin >> 3;
+  const int log_id = xcd < rem ? xcd * (per + 1) + slot : rem * (per + 1) + (xcd - rem) * per + slot;
+  const int bx = log_id % gx, byz = log_id / gx, by = byz % gy, bz = byz / gy;
+  const int p0 = by * BP, q0 = bx * BQ;
+  const int m_begin = bz * p.m_per_split;
   const int m_end = min(p.M, m_begin + p.m_per_split);
 
   // D staging: this thread always loads columns p0 + chp*4 .. +3
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
 
   float4 rd[2][NP], rx[2][NQ];
   float4 bsum = make_float4(0.f, 0.f, 0.f, 0.f);
-  const bool do_bias = (blockIdx.x == 0) && (p.part_b != nullptr);
+  const bool do_bias = (bx == 0) && (p.part_b != nullptr);
   const float bsel = do_bias ? 1.f : 0.f;
 
   // Row table: entry r of Rt[s & 1] describes reduction row m_begin + 32*s + r of staging step s:
@@ -250,7 +260,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   }
 
   // ---- store the partial tile: lane holds, per (a, e), QT consecutive q ----
-  float *part = p.part + (long long)blockIdx.z * p.P * p.Qld;
+  float *part = p.part + (long long)bz * p.P * p.Qld;
 #pragma unroll
   for (int a = 0; a < PT; ++a) {
 #pragma unroll
@@ -275,7 +285,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
     if (t < BP && p0 + t < p.P) {
       float s = 0.f;
       for (int r = 0; r < RP; ++r) s += red[r * BP + t];
-      p.part_b[(long long)blockIdx.z * p.P + p0 + t] = s;
+      p.part_b[(long long)bz * p.P + p0 + t] = s;
     }
   }
 }
