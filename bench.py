@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--no-prof", action="store_true")
     ap.add_argument("--lr", type=float, default=None, help="override the configuration's learning rate")
     ap.add_argument("--trace-loss", action="store_true", help="print every layer's loss after each step (syncs)")
+    ap.add_argument("--traffic-calib", action="store_true",
+                    help="only run 5 plain copies of 1 GiB (nf_cache_read, contiguous rows): the known-size kernel "
+                         "the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -68,6 +71,16 @@ def main():
     nf.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.traffic_calib:
+        rows, se = 4096, 65536  # 4096 rows of 256 KiB: reads 1 GiB, writes 1 GiB per launch
+        src = torch.ones((rows, se), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            nf.nf_cache_read(src, None, rows, se, 0, None, rows, dst, None)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_calib": "cache_copy_kernel", "launches": 5, "read_bytes": rows * se * 4,
+                          "write_bytes": rows * se * 4}))
+        return
     cfg = workloads.config(args.config)
     if args.lr is not None:
         cfg.lr = args.lr
