@@ -27,6 +27,15 @@ sys.path.insert(0, ROOT)
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 
+# HBM-side bytes per launch (fabric reads + writes) of the kernels that can dominate the default
+# workload, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` passes over this script, each
+# scaled by what the same counter reads for a plain 1 GiB copy (`--traffic-calib`): FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0.  Averages over the launches of one step; summary under profiles/.
+TRAFFIC_BYTES_PER_LAUNCH = {
+    ("cfg3", "igemm_wgrad_fast_128x128"): 62.7e6 + 37.9e6,
+    ("cfg3", "igemm_fwd_fast_128x128"): 47.9e6 + 16.8e6,
+}
+
 
 def layer_flops(ls, B, n_classes):
     """Algorithmic FLOPs of one local step: fwd + wgrad for the layer (and projection),
@@ -218,7 +227,8 @@ def main():
             ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
             roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": round(ach, 2),
                         "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_F32_PEAK_TFLOPS, 4),
-                        "traffic": None, "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
+                        "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, dom["kernel"])),
+                        "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                         "measured_over": f"{psteps} further steps with one HIP-event pair per kernel launch"}
         else:
             ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
