@@ -45,6 +45,13 @@ CASES = {
     "many_m_tiles": (S(16, 16, 16, 64, 16), 40, 10),
     "conv1x1": (S(16, 6, 6, 24, 8, R=1, pad=0), 4, 10),
     "rect_5x3_filter": (S(8, 9, 8, 16, 8, R=5, S_=3, pad=1), 3, 10),
+    # skinny heads: split reduction of the aux conv forward (long reduction, few row tiles) and
+    # the 4x4x1-MFMA weight gradient in each of its (groups, channels-per-lane) shapes
+    "skinny_a4_c256_split": (S(16, 6, 6, 256, 4), 5, 10),
+    "skinny_a8_c128_split": (S(8, 8, 8, 128, 8), 6, 10),
+    "skinny_a12_c136_ragged": (S(8, 5, 7, 136, 12), 3, 10),
+    "skinny_a16_c64_pool": (S(8, 12, 12, 64, 16, pool=(2, 2, 0)), 4, 10),
+    "skinny_a4_c64_one_row_images": (S(8, 1, 9, 64, 4), 7, 10),
 }
 
 
