@@ -179,8 +179,10 @@ def _cfg4():
 def _cfg5():
     layers = resnet_layers([3, 4, 6, 3], in_shape=(3, 128, 128), stem="7x7")
     blocks = _assign(layers, [1, 6, 8, 6, 6, 6], [32, 64, 128, 256, 512, 512], [32, 32, 16, 8, 8, 4])
-    return Config("cfg5_resnet34", (3, 128, 128), 200, layers, blocks, 0.001, 0.9, 4, 16384, notes=_LR_NOTE,
-                  extra={"memory_budget_bytes": 16 << 30})
+    # 33 un-normalised layers on 128x128 inputs: activations reach ~4e3 at the deepest heads and
+    # lr = 0.001 still ends in inf/NaN there after a few steps (measured); 1e-5 stays finite
+    return Config("cfg5_resnet34", (3, 128, 128), 200, layers, blocks, 1e-5, 0.9, 4, 16384,
+                  notes=_LR_NOTE.replace("lr 0.001", "lr 1e-5"), extra={"memory_budget_bytes": 16 << 30})
 
 
 _BUILDERS = {"cfg1": _cfg1, "cfg2": _cfg2, "cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}
