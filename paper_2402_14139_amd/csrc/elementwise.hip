@@ -100,6 +100,43 @@ __global__ __launch_bounds__(ET) void maxpool_bwd_kernel(const float *__restrict
   }
 }
 
+// ---- epilogue of a split forward-type contraction: sum of the parts in order, bias, identity
+// shortcut, ReLU, mask (Eq. 1 after the convolution; data gradient of beta_n) ----
+template <int V>
+__global__ __launch_bounds__(ET) void fwd_finish_kernel(const float *__restrict__ part, int splits, long long total,
+                                                        int N, const float *__restrict__ bias,
+                                                        const float *__restrict__ addsrc,
+                                                        const float *__restrict__ mask, int relu,
+                                                        float *__restrict__ out) {
+  const long long i = ((long long)blockIdx.x * ET + threadIdx.x) * V;
+  if (i >= total) return;
+  float v[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) v[e] = 0.f;
+  for (int z = 0; z < splits; ++z) {
+    const float *src = part + (long long)z * total + i;
+    if constexpr (V == 4) {
+      const float4 t = *reinterpret_cast<const float4 *>(src);
+      v[0] += t.x, v[1] += t.y, v[2] += t.z, v[3] += t.w;
+    } else {
+      v[0] += src[0];
+    }
+  }
+  const int n = (int)(i % N);
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    if (bias) v[e] += bias[n + e];
+    if (addsrc) v[e] += addsrc[i + e];
+    if (relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
+    if (mask) v[e] = mask[i + e] > 0.f ? v[e] : 0.f;
+  }
+  if constexpr (V == 4) {
+    *reinterpret_cast<float4 *>(out + i) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+    out[i] = v[0];
+  }
+}
+
 // ---- update line of Algorithm 2: blockIdx.y = tensor, grid-stride over its elements ----
 __global__ __launch_bounds__(ET) void sgd_kernel(SgdTensors t) {
   const int ti = blockIdx.y;
@@ -178,6 +215,18 @@ hipError_t launch_maxpool_bwd(const float *dY, const float *Y, const uint8_t *ar
   else
     hipLaunchKernelGGL(maxpool_bwd_kernel<1>, dim3(nblocks((long long)B * Ho * Wo * K)), dim3(ET), 0, st, dY, Y, arg,
                        dZ, B, Ho, Wo, K, Hp, Wp, pk, ps, pp);
+  return hipGetLastError();
+}
+
+hipError_t launch_fwd_finish(const float *part, int splits, long long M, int N, const float *bias,
+                             const float *addsrc, const float *mask, int relu, float *out, hipStream_t st) {
+  const long long total = M * N;
+  if (N % 4 == 0)
+    hipLaunchKernelGGL(fwd_finish_kernel<4>, dim3(nblocks(total / 4)), dim3(ET), 0, st, part, splits, total, N, bias,
+                       addsrc, mask, relu, out);
+  else
+    hipLaunchKernelGGL(fwd_finish_kernel<1>, dim3(nblocks(total)), dim3(ET), 0, st, part, splits, total, N, bias,
+                       addsrc, mask, relu, out);
   return hipGetLastError();
 }
 

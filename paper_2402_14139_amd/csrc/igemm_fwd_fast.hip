@@ -375,16 +375,28 @@ hipError_t launch_cfg(const FwdProblem &p, FastAux q, hipStream_t st) {
 
 }  // namespace
 
-// Skinny outputs (few filters) with a long reduction leave most of the chip idle: M/64 or M/128
-// workgroups, each a long serial chain of load -> LDS -> MFMA steps.  Splitting the reduction
-// multiplies the workgroups; the consumer adds the partial sums in a fixed order.
-int igemm_fwd_pick_ksplits(int M, int N, int RSC, int C, int taps) {
-  if (C % 4 || taps > 32 || N > 32) return 1;
-  const int tiles = N > 16 ? (M + 127) / 128 : (M + 63) / 64;
-  const int nkb = (RSC + 31) / 32;
-  int s = 1024 / (tiles > 0 ? tiles : 1);
-  if (s > nkb / 16) s = nkb / 16;
-  if (s > 16) s = 16;
+// Few output tiles with a long reduction leave most of the chip idle: each workgroup is a long
+// serial chain of load -> LDS -> MFMA steps.  Splitting the reduction multiplies the workgroups;
+// the consumer adds the partial sums in a fixed order.  Two cases: skinny outputs (few filters:
+// the aux heads) and small M*N (late layers at 2x2 .. 4x4 resolution).  Kg = whole reduction
+// length (filter taps * channels + projection channels).
+int igemm_fwd_pick_ksplits(int M, int N, int Kg, int C, int taps) {
+  if (C % 4 || taps > 32) return 1;
+  const int nkb = (Kg + 31) / 32;
+  if (N <= 32) {
+    const int tiles = N > 16 ? (M + 127) / 128 : (M + 63) / 64;
+    int s = 1024 / (tiles > 0 ? tiles : 1);
+    if (s > nkb / 16) s = nkb / 16;
+    if (s > 16) s = 16;
+    return s > 1 ? s : 1;
+  }
+  // tile shape as launch_igemm_fwd_fast picks it
+  const int bm = (N > 64 && Kg > 160) ? 128 : (Kg <= 160 ? 64 : 128), bn = (N > 64 && Kg > 160) ? 128 : 64;
+  const int tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  if (tiles >= 192) return 1;
+  int s = 256 / tiles;
+  if (s > nkb / 8) s = nkb / 8;
+  if (s > 32) s = 32;
   return s > 1 ? s : 1;
 }
 

@@ -98,7 +98,8 @@ WgradProblem aux_wgrad_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
 struct WsLayout {
   size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
-  int ksplits_aux;  // reduction splits of the aux convolution forward (partials alias `part`)
+  // reduction splits of the forward-type contractions (1 = none); their partial sums alias `part`
+  int ksplits_aux, ksplits_layer, ksplits_dgrad;
 };
 
 WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B) {
@@ -116,6 +117,10 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
   // pre-pool activation in the forward, dL/d(conv output) in the backward: never live together
   w.T_dZ = take((pooled || a) ? conv_out * f : 0);
   w.arg = take(pooled ? emitted : 0);
+  const int Kl = d->R * d->S * d->C_in + (d->skip_kind == 2 ? d->skip_C : 0);
+  w.ksplits_layer = igemm_fwd_pick_ksplits(B * ld.Ho * ld.Wo, d->C_out, Kl, d->C_in, d->R * d->S);
+  size_t pmax = w.ksplits_layer > 1 ? (size_t)w.ksplits_layer * conv_out : 0;
+  w.ksplits_aux = w.ksplits_dgrad = 1;
   if (a) {
     const size_t u = (size_t)B * ad.Hu * ad.Wu * a->A;
     w.U = take(u * f);
@@ -126,22 +131,27 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     w.dU = take(u * f);
     w.WaT = take((size_t)a->A * a->R * a->S * a->C_in * f);
     w.dY = take(pooled ? emitted * f : 0);
-    const int Qa = a->R * a->S * a->C_in, Ql = d->R * d->S * d->C_in + (d->skip_kind == 2 ? d->skip_C : 0);
+    const int Qa = a->R * a->S * a->C_in;
     w.Qld_aux = (Qa + 3) / 4 * 4;
-    w.Qld_layer = (Ql + 3) / 4 * 4;
+    w.Qld_layer = (Kl + 3) / 4 * 4;
     w.splits_aux = igemm_wgrad_small_applicable(aux_wgrad_shape(a, ad, B))
                        ? igemm_wgrad_small_splits(a->A, a->C_in, B, a->H_in)
                        : wgrad_pick_splits(a->A, Qa, B * ad.Hu * ad.Wu);
-    w.splits_layer = wgrad_pick_splits(d->C_out, Ql, B * ld.Ho * ld.Wo);
+    w.splits_layer = wgrad_pick_splits(d->C_out, Kl, B * ld.Ho * ld.Wo);
     // split partials of the two weight gradients live side by side: one launch reduces both
     const size_t pa = (size_t)w.splits_aux * a->A * w.Qld_aux, pl = (size_t)w.splits_layer * d->C_out * w.Qld_layer;
+    if (pl > pmax) pmax = pl;
+    // partials of the aux forward are dead before the backward; those of the data gradient are
+    // dead before the layer's weight gradient overwrites them
     w.ksplits_aux = igemm_fwd_pick_ksplits(B * ad.Hu * ad.Wu, a->A, Qa, a->C_in, a->R * a->S);
-    const size_t pk = w.ksplits_aux > 1 ? (size_t)w.ksplits_aux * u : 0;  // aux forward partials: dead before the backward
-    w.part = take((pl > pk ? pl : pk) * f);
+    if (w.ksplits_aux > 1 && (size_t)w.ksplits_aux * u > pmax) pmax = (size_t)w.ksplits_aux * u;
+    w.ksplits_dgrad = igemm_fwd_pick_ksplits(B * a->H_in * a->W_in, a->C_in, a->R * a->S * a->A, a->A, a->R * a->S);
+    if (w.ksplits_dgrad > 1 && (size_t)w.ksplits_dgrad * emitted > pmax) pmax = (size_t)w.ksplits_dgrad * emitted;
     w.part_b = take((size_t)w.splits_layer * d->C_out * f);
     w.part_aux = take(pa * f);
     w.part_b_aux = take((size_t)w.splits_aux * a->A * f);
   }
+  w.part = take(pmax * f);
   w.total = off ? off : ALIGN;
   return w;
 }
@@ -210,6 +220,24 @@ int32_t enqueue_fwd(const FwdProblem &f, hipStream_t st) {
   return NF_OK;
 }
 
+// forward-type contraction into `out`; with ksplits > 1 (and the fast path available) the
+// reduction is split into `part` and a small kernel applies the epilogue
+int32_t enqueue_fwd_split(FwdProblem f, float *out, int ksplits, float *part, hipStream_t st) {
+  if (ksplits > 1 && igemm_fwd_fast_applicable(f)) {
+    const float *bias = f.bias, *addsrc = f.addsrc, *mask = f.mask;
+    const int relu = f.relu;
+    f.ksplits = ksplits, f.out = part;
+    const int32_t rc = enqueue_fwd(f, st);
+    if (rc) return rc;
+    const double mn = (double)f.M * f.N;
+    NF_RUN(st, "fwd_finish", 0.0, 4.0 * mn * (ksplits + 1.0 + (addsrc ? 1.0 : 0.0) + (mask ? 1.0 : 0.0)),
+           launch_fwd_finish(part, ksplits, f.M, f.N, bias, addsrc, mask, relu, out, st));
+    return NF_OK;
+  }
+  f.ksplits = 0, f.out = out;
+  return enqueue_fwd(f, st);
+}
+
 int32_t enqueue_wgrad(const WgradProblem &g, hipStream_t st) {
   const double B = (double)g.M / ((double)g.Ho * g.Wo);
   const double flops = 2.0 * g.M * g.P * g.Q;
@@ -243,8 +271,8 @@ int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const 
   f.relu = 1;
   f.M = B * ld.Ho * ld.Wo, f.RSC = d->R * d->S * d->C_in, f.Kg = f.RSC + f.Cs;
   f.div_howo = FastDiv(ld.Ho * ld.Wo), f.div_wo = FastDiv(ld.Wo);
-  f.out = pooled ? wsf(ws, w.T_dZ) : y;
-  int32_t rc = enqueue_fwd(f, st);
+  float *conv_out = pooled ? wsf(ws, w.T_dZ) : y;
+  int32_t rc = enqueue_fwd_split(f, conv_out, w.ksplits_layer, wsf(ws, w.part), st);
   if (rc) return rc;
   if (pooled) {
     const double pre = (double)B * ld.Ho * ld.Wo * d->C_out, post = (double)B * ld.Hp * ld.Wp * d->C_out;
@@ -329,8 +357,7 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     f.M = B * a->H_in * a->W_in, f.RSC = a->R * a->S * a->A, f.Kg = f.RSC;
     f.div_howo = FastDiv(a->H_in * a->W_in), f.div_wo = FastDiv(a->W_in);
     f.mask = pooled ? nullptr : y;
-    f.out = pooled ? wsf(ws, w.dY) : dZ;
-    const int32_t rc = enqueue_fwd(f, st);
+    const int32_t rc = enqueue_fwd_split(f, pooled ? wsf(ws, w.dY) : dZ, w.ksplits_dgrad, wsf(ws, w.part), st);
     if (rc) return rc;
     if (pooled) {
       const double pre = (double)B * ld.Ho * ld.Wo * d->C_out, post = (double)B * ld.Hp * ld.Wp * d->C_out;

@@ -41,7 +41,11 @@ struct FwdProblem {
   int ksplits;
 };
 // how many reduction splits a skinny forward-type contraction should use (1 = none)
-int igemm_fwd_pick_ksplits(int M, int N, int RSC, int C, int taps);
+int igemm_fwd_pick_ksplits(int M, int N, int Kg, int C, int taps);
+// out[m][n] = act(sum_z part[z][m][n] + bias[n] + addsrc[m][n]) zeroed where mask[m][n] <= 0:
+// the epilogue of a forward-type contraction whose reduction was split
+hipError_t launch_fwd_finish(const float *part, int splits, long long M, int N, const float *bias,
+                             const float *addsrc, const float *mask, int relu, float *out, hipStream_t st);
 // `*kernel` receives a static string naming the tile configuration that was launched
 hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **kernel);
 // branch-free buffer-load variant (igemm_fwd_fast.hip); launch_igemm_fwd picks it when applicable
