@@ -384,14 +384,14 @@ int igemm_fwd_pick_ksplits(int M, int N, int Kg, int C, int taps) {
   if (C % 4 || taps > 32) return 1;
   const int nkb = (Kg + 31) / 32;
   if (N <= 32) {
-    const int tiles = N > 16 ? (M + 127) / 128 : (M + 63) / 64;
+    const int tiles = (M + 63) / 64;
     int s = 1024 / (tiles > 0 ? tiles : 1);
     if (s > nkb / 16) s = nkb / 16;
     if (s > 16) s = 16;
     return s > 1 ? s : 1;
   }
   // tile shape as launch_igemm_fwd_fast picks it
-  const int bm = (N > 64 && Kg > 160) ? 128 : (Kg <= 160 ? 64 : 128), bn = (N > 64 && Kg > 160) ? 128 : 64;
+  const int bm = (N > 64 && Kg > 160) ? 128 : 64, bn = bm;
   const int tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
   if (tiles >= 192) return 1;
   int s = 256 / tiles;
@@ -422,18 +422,15 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
     *kernel = "igemm_fwd_fast_128x128";
     return launch_cfg<128, 128, 32, 2, 2, 32>(p, q, st);
   }
-  if (p.N > 32 && p.Kg <= 160) {
-    // one to five reduction steps: bound by the output stream; small tiles keep more waves in flight
+  if (p.N > 32) {
+    // at most 64 columns, or one to five reduction steps (bound by the output stream): small
+    // tiles keep more workgroups in flight (measured 7-9 % faster than 128x64 at N = 64)
     *kernel = "igemm_fwd_fast_64x64";
     return launch_cfg<64, 64, 32, 2, 2, 32>(p, q, st);
   }
-  if (p.N > 32) {
-    *kernel = "igemm_fwd_fast_128x64";
-    return launch_cfg<128, 64, 32, 2, 2, 32>(p, q, st);
-  }
   if (p.N > 16) {
-    *kernel = "igemm_fwd_fast_128x32";
-    return launch_cfg<128, 32, 32, 4, 1, 32>(p, q, st);
+    *kernel = "igemm_fwd_fast_64x32";
+    return launch_cfg<64, 32, 32, 4, 1, 16>(p, q, st);  // 16x16x4 MFMA, waves of 16 x 32
   }
   *kernel = "igemm_fwd_fast_64x16";
   if (p.ksplits > 1) return launch_cfg<64, 16, 32, 4, 1, 16>(p, q, st);
