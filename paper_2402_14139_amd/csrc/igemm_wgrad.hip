@@ -414,8 +414,8 @@ struct TileChoice {
 };
 inline TileChoice pick_tile(int P) {
   if (P > 64) return {128, 128};
-  if (P > 32) return {64, 128};
-  return {32, 256};
+  if (P > 32) return {64, 64};
+  return {32, 128};
 }
 
 template <int BP, int BQ, int WP, int WQ>

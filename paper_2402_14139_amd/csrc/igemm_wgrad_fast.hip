@@ -321,11 +321,11 @@ hipError_t launch_igemm_wgrad_fast(const WgradProblem &p0, hipStream_t st, const
     return launch_cfg<128, 128, 2, 2>(p, st);
   }
   if (p.P > 32) {
-    *kernel = "igemm_wgrad_fast_64x128";
-    return launch_cfg<64, 128, 2, 2>(p, st);
+    *kernel = "igemm_wgrad_fast_64x64";
+    return launch_cfg<64, 64, 2, 2>(p, st);
   }
-  *kernel = "igemm_wgrad_fast_32x256";
-  return launch_cfg<32, 256, 1, 4>(p, st);
+  *kernel = "igemm_wgrad_fast_32x128";
+  return launch_cfg<32, 128, 1, 4>(p, st);
 }
 
 }  // namespace nf
