@@ -53,7 +53,10 @@ struct Frag<4> {
 };
 
 // BP x BQ output tile, WP x WQ waves, each wave (32*PT) x (32*QT); LDS tiles [m][p], [m][q].
-template <int BP, int BQ, int WP, int WQ, bool PROJ>
+// PROJ 0: no projection columns.  1: a tile may hold taps and projection channels (RSC not a
+// multiple of BQ): two loads per row, one of them out of range.  2: RSC is a multiple of BQ, a
+// tile is all taps or all projection channels: one load, its source picked per workgroup.
+template <int BP, int BQ, int WP, int WQ, int PROJ>
 __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProblem p) {
   constexpr int TP = BP / WP, TQ = BQ / WQ;
   constexpr int PT = TP / 32, QT = TQ / 32;
@@ -94,7 +97,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   // fixed projection channel
   const int chq = t % CQ, rowq = t / CQ;
   const int qcol = q0 + chq * 4;
-  const bool is_tap = qcol < p.RSC, is_proj = PROJ && !is_tap && qcol < p.Q;
+  const bool is_tap = qcol < p.RSC, is_proj = PROJ != 0 && !is_tap && qcol < p.Q;
+  const bool tile_proj = PROJ == 2 && q0 >= p.RSC;  // uniform
   int qr = 0, qs = 0, qc = 0;
   if (is_tap) {
     const int tap = qcol / p.C;
@@ -110,6 +114,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   const __amdgpu_buffer_rsrc_t rsd = __builtin_amdgcn_make_buffer_rsrc((void *)p.d, 0, p.d_bytes, RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t rsxs = __builtin_amdgcn_make_buffer_rsrc((void *)p.xs, 0, p.xs_bytes, RSRC_FLAGS);
+  // PROJ == 2: the one source of this workgroup's X columns
+  const __amdgpu_buffer_rsrc_t rs_sel = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(tile_proj ? p.xs : p.x), 0, tile_proj ? p.xs_bytes : p.x_bytes, RSRC_FLAGS);
+  const int proj_mask = tile_proj ? -1 : 0;
 
   float4 rd[2][NP], rx[2][NQ];
   float4 bsum = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -131,7 +139,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
     e.x = ((img * p.H + hi0) * p.W + wi0) * p.C * 4;
     e.y = m < m_end ? hi0 : -(1 << 20);
     e.z = wi0;
-    e.w = PROJ ? ((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs * 4 : 0;
+    e.w = PROJ != 0 ? ((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs * 4 : 0;
     Rt[s & 1][t & (BKM - 1)] = e;
   };
 
@@ -150,11 +158,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
       const bool ok = is_tap & ((unsigned)(e.y + qr) < (unsigned)p.H) & ((unsigned)(e.z + qs) < (unsigned)p.W);
       // the offset is formed unconditionally and pushed out of range by its top bit: a select would
       // let the compiler sink the table read into a branch
-      float4 v = bload(rsx, (e.x + xtap_off) | (ok ? 0 : OOB));
-      if constexpr (PROJ) {
-        const bool okp = is_proj & (e.y > -(1 << 19));
-        const float4 u = bload(rsxs, (e.w + qc * 4) | (okp ? 0 : OOB));
-        v.x += u.x, v.y += u.y, v.z += u.z, v.w += u.w;  // one of the two is all zeros
+      float4 v;
+      if constexpr (PROJ == 2) {
+        // bit selects with the workgroup-uniform mask: a ?: here would be turned into branches
+        const int okp = (is_proj & (e.y > -(1 << 19))) ? 0 : OOB, okt = ok ? 0 : OOB;
+        const int off = (((e.w + qc * 4) | okp) & proj_mask) | (((e.x + xtap_off) | okt) & ~proj_mask);
+        v = bload(rs_sel, off);
+      } else {
+        v = bload(rsx, (e.x + xtap_off) | (ok ? 0 : OOB));
+        if constexpr (PROJ == 1) {
+          const bool okp = is_proj & (e.y > -(1 << 19));
+          const float4 u = bload(rsxs, (e.w + qc * 4) | (okp ? 0 : OOB));
+          v.x += u.x, v.y += u.y, v.z += u.z, v.w += u.w;  // one of the two is all zeros
+        }
       }
       rx[set][i] = v;
     }
@@ -204,7 +220,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   //     LDS writes of step s+1 (loaded one step ago) over the later ones;
   //   barrier; first fragments of step s+1; MFMAs of the last sub-step.
   constexpr int NM = 2 * PT * QT;  // MFMAs per sub-step
-  constexpr int NV = NP + NQ * (PROJ ? 2 : 1);  // buffer loads per step
+  constexpr int NV = NP + NQ * (PROJ == 1 ? 2 : 1);  // buffer loads per step
   constexpr int NW = NP + NQ;                   // LDS writes per step
   auto step = [&](int s, auto par_tag) {
     constexpr int par = decltype(par_tag)::value;
@@ -293,10 +309,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
 template <int BP, int BQ, int WP, int WQ>
 hipError_t launch_cfg(const WgradProblem &p, hipStream_t st) {
   dim3 grid((p.Q + BQ - 1) / BQ, (p.P + BP - 1) / BP, p.splits);
-  if (p.Cs)
-    hipLaunchKernelGGL((igemm_wgrad_fast_kernel<BP, BQ, WP, WQ, true>), grid, dim3(NTHREADS), 0, st, p);
+  if (p.Cs && p.RSC % BQ == 0)
+    hipLaunchKernelGGL((igemm_wgrad_fast_kernel<BP, BQ, WP, WQ, 2>), grid, dim3(NTHREADS), 0, st, p);
+  else if (p.Cs)
+    hipLaunchKernelGGL((igemm_wgrad_fast_kernel<BP, BQ, WP, WQ, 1>), grid, dim3(NTHREADS), 0, st, p);
   else
-    hipLaunchKernelGGL((igemm_wgrad_fast_kernel<BP, BQ, WP, WQ, false>), grid, dim3(NTHREADS), 0, st, p);
+    hipLaunchKernelGGL((igemm_wgrad_fast_kernel<BP, BQ, WP, WQ, 0>), grid, dim3(NTHREADS), 0, st, p);
   return hipGetLastError();
 }
 
