@@ -30,7 +30,6 @@ namespace {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
-constexpr int OOB = (int)0x80000000;    // offset no buffer of < 2 GiB contains
 constexpr int RSRC_FLAGS = 0x00020000;  // raw buffer, 32-bit data format
 
 template <int V>
@@ -64,8 +63,9 @@ struct SmallAux {
 template <int G, int V, int RING>
 __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, SmallAux q) {
   constexpr int NACC = G * 9 * V;              // accumulators (4 registers each) per lane
-  __shared__ float red[2][NACC * 4][64];       // two waves' accumulators
+  __shared__ float4 red[2][NACC][64];          // two waves' accumulators
   __shared__ float redb[4][G][4];
+  __shared__ int4 desc[4][128];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -73,13 +73,10 @@ __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, Sma
 
   // this lane's channels and output-channel rows
   const int c = blockIdx.x * (64 * V) + lane * V;
-  const int lane_x = c * 4;
-  const int lane_oob = c < p.C ? 0 : OOB;
   // output channels of this workgroup: pbase + g + G*i (group g, row i); lane row i = lane & 3
   const int pbase = blockIdx.y * (4 * G);
   const int lane_p = pbase + G * (lane & 3);          // first of the lane's G consecutive channels
-  const int lane_d = lane_p * 4;
-  const int lane_d_oob = lane_p < p.P ? 0 : OOB;      // P % G == 0 (launcher): all G or none
+  // P % G == 0 (launcher): a lane's G channels are all inside P or all outside
 
   const __amdgpu_buffer_rsrc_t rsd = __builtin_amdgcn_make_buffer_rsrc((void *)p.d, 0, p.d_bytes, RSRC_FLAGS);
   const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, RSRC_FLAGS);
@@ -92,36 +89,41 @@ __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, Sma
   const int row_end = min(wg_row1, row_begin + rpw);
   const int L = (row_end - row_begin) * W2;  // stream elements
 
-  // load cursor (uniform): stream element -> (image, image row, position in the padded row)
-  int cur_e = 0, cur_t = 0, cur_n = row_begin / p.H, cur_h = row_begin - (row_begin / p.H) * p.H;
-
-  float xr[RING][3][V], dr[RING][G];
-  // Everything about the cursor is uniform and branch-free: offsets are formed unconditionally and
-  // pushed out of range by their top bit (a select would be turned into a branch, and a branch in
-  // the main loop makes the compiler shuffle the accumulators through other registers).
-  auto load_elem = [&](int slot) {
-    const bool live = cur_e < L;
-    const int col = cur_t - 1;
+  // Descriptor table (per wave, in LDS): for stream element e the byte offsets of its three
+  // window-row loads and of its dU load, already out of range (bit 30: operands are < 1 GiB, and
+  // the sum of two such markers still is) where there is no data.  One lane decodes one element,
+  // 64 elements at a time, ahead of the loads; the main loop then pays one broadcast LDS read and
+  // four adds per element instead of ~60 scalar instructions -- with 8-cycle MFMAs, the
+  // instructions between them are what the step time is made of.
+  constexpr int OOB30 = 0x40000000;
+  const int lane_xo = c < p.C ? c * 4 : OOB30;
+  const int lane_do = lane_p < p.P ? lane_p * 4 : OOB30;
+  auto make_desc = [&](int chunk) {  // elements [64*chunk, 64*chunk + 64)
+    const int e = chunk * 64 + lane;
+    const int er = e / W2, t = e - er * W2;
+    const int row = row_begin + er;
+    const int n = row / p.H, h = row - n * p.H;
+    const bool live = e < L;
+    const int col = t - 1;
     const bool col_ok = live & ((unsigned)col < (unsigned)p.W);
-    const int pix = (cur_n * p.H + cur_h) * p.W + cur_t;  // pixel (row, w = t)
-#pragma unroll
-    for (int r = 0; r < 3; ++r) {
-      const int hh = cur_h - 1 + r;
-      const bool ok = col_ok & ((unsigned)hh < (unsigned)p.H);
-      const int soff = ((pix + (r - 1) * p.W - 1) * p.C * 4) | (ok ? 0 : OOB);
-      VLoad<V>::ld(rsx, (soff + lane_x) | lane_oob, xr[slot][r]);
-    }
-    const bool d_ok = live & (cur_t < p.W);
-    const int doff = (pix * p.P * 4) | (d_ok ? 0 : OOB);
-    VLoad<G>::ld(rsd, (doff + lane_d) | lane_d_oob, dr[slot]);
-    // advance
-    ++cur_e, ++cur_t;
-    const int wrap_t = cur_t == W2 ? 1 : 0;
-    cur_t = wrap_t ? 0 : cur_t;
-    cur_h += wrap_t;
-    const int wrap_h = cur_h == p.H ? 1 : 0;
-    cur_h = wrap_h ? 0 : cur_h;
-    cur_n += wrap_h;
+    const int pix = (n * p.H + h) * p.W + t;  // pixel (row, w = t)
+    int4 dsc;
+    dsc.x = (col_ok & (h >= 1)) ? (pix - p.W - 1) * p.C * 4 : OOB30;
+    dsc.y = col_ok ? (pix - 1) * p.C * 4 : OOB30;
+    dsc.z = (col_ok & (h + 1 < p.H)) ? (pix + p.W - 1) * p.C * 4 : OOB30;
+    dsc.w = (live & (t < p.W)) ? pix * p.P * 4 : OOB30;
+    desc[wave][e & 127] = dsc;
+  };
+
+  int cur_e = 0;  // load cursor (uniform)
+  float xr[RING][3][V], dr[RING][G];
+  auto load_elem = [&](int slot) {
+    const int4 dsc = desc[wave][cur_e & 127];  // same address in every lane
+    VLoad<V>::ld(rsx, dsc.x + lane_xo, xr[slot][0]);
+    VLoad<V>::ld(rsx, dsc.y + lane_xo, xr[slot][1]);
+    VLoad<V>::ld(rsx, dsc.z + lane_xo, xr[slot][2]);
+    VLoad<G>::ld(rsd, dsc.w + lane_do, dr[slot]);
+    ++cur_e;
   };
 
   floatx4 acc[G][3][3][V];
@@ -137,95 +139,104 @@ __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, Sma
 #pragma unroll
   for (int g = 0; g < G; ++g) bsum[g] = 0.f;
 
-  // prologue: elements 0 .. RING-2
+  // prologue: descriptors of the first 64 elements, then elements 0 .. RING-2
+  make_desc(0);
 #pragma unroll
   for (int i = 0; i + 1 < RING; ++i) load_elem(i);
 
   // step j (ring slot j % RING) uses elements j, j+1, j+2 and refills the slot of element j-1
-  for (int j0 = 0; j0 < L; j0 += RING) {
+  static_assert(64 % RING == 0, "a descriptor chunk is a whole number of ring rounds");
+  for (int cb = 0; cb < L; cb += 64) {
+    make_desc((cb >> 6) + 1);  // the cursor runs RING-1 elements ahead: next chunk's descriptors now
+    const int rounds = min(64 / RING, (L - cb + RING - 1) / RING);
+    for (int rd = 0; rd < rounds; ++rd) {
 #pragma unroll
-    for (int i = 0; i < RING; ++i) {
-      load_elem((i + RING - 1) % RING);
+      for (int i = 0; i < RING; ++i) {
+        load_elem((i + RING - 1) % RING);
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float a = dr[i][g];
-        bsum[g] += a;
+        for (int g = 0; g < G; ++g) {
+          const float a = dr[i][g];
+          bsum[g] += a;
 #pragma unroll
-        for (int s = 0; s < 3; ++s)
+          for (int s = 0; s < 3; ++s)
 #pragma unroll
-          for (int r = 0; r < 3; ++r)
+            for (int r = 0; r < 3; ++r)
 #pragma unroll
-            for (int v = 0; v < V; ++v)
-              acc[g][r][s][v] = __builtin_amdgcn_mfma_f32_4x4x1f32(a, xr[(i + s) % RING][r][v], acc[g][r][s][v], 0, 0, 0);
+              for (int v = 0; v < V; ++v)
+                acc[g][r][s][v] =
+                    __builtin_amdgcn_mfma_f32_4x4x1f32(a, xr[(i + s) % RING][r][v], acc[g][r][s][v], 0, 0, 0);
+        }
       }
     }
   }
 
-  // ---- add the four waves' accumulators in a fixed order: (w0 + w2) + (w1 + w3) ----
-  auto put = [&](int slot) {
-    int k = 0;
+  // ---- add the four waves' accumulators in a fixed order, (w0 + w2) + (w1 + w3), through LDS
+  // with 16-byte accesses; the last addition and the store of the partial tile are shared by
+  // waves 0 and 1 (each takes half of the (group, tap) pairs; a + b == b + a exactly) ----
+  constexpr int NGT = G * 9, KH = (NGT + 1) / 2;  // (group, tap) pairs; size of the first half
+  // part 0: pairs [0, KH), 1: pairs [KH, NGT), 2: all
+  auto in_part = [&](int gt, int part) { return part == 2 || (part == 0 ? gt < KH : gt >= KH); };
+  auto put = [&](int slot, int part) {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int gt = 0; gt < NGT; ++gt)
 #pragma unroll
-      for (int r = 0; r < 3; ++r)
-#pragma unroll
-        for (int s = 0; s < 3; ++s)
-#pragma unroll
-          for (int v = 0; v < V; ++v)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) red[slot][k++][lane] = acc[g][r][s][v][e];
+      for (int v = 0; v < V; ++v)
+        if (in_part(gt, part)) {
+          const floatx4 t = acc[gt / 9][(gt % 9) / 3][gt % 3][v];
+          red[slot][gt * V + v][lane] = make_float4(t[0], t[1], t[2], t[3]);
+        }
   };
-  auto add = [&](int slot) {
-    int k = 0;
+  auto add = [&](int slot, int part) {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int gt = 0; gt < NGT; ++gt)
 #pragma unroll
-      for (int r = 0; r < 3; ++r)
-#pragma unroll
-        for (int s = 0; s < 3; ++s)
-#pragma unroll
-          for (int v = 0; v < V; ++v)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[g][r][s][v][e] += red[slot][k++][lane];
+      for (int v = 0; v < V; ++v)
+        if (in_part(gt, part)) {
+          const float4 t = red[slot][gt * V + v][lane];
+          floatx4 &d = acc[gt / 9][(gt % 9) / 3][gt % 3][v];
+          d[0] += t.x, d[1] += t.y, d[2] += t.z, d[3] += t.w;
+        }
   };
   if (lane < 4) {
 #pragma unroll
     for (int g = 0; g < G; ++g) redb[wave][g][lane] = bsum[g];
   }
-  if (wave >= 2) put(wave - 2);
+  if (wave >= 2) put(wave - 2, 2);
   __syncthreads();
-  if (wave < 2) add(wave);
+  if (wave < 2) add(wave, 2);
   __syncthreads();
-  if (wave == 1) put(0);
+  if (wave == 1) put(0, 0);
+  if (wave == 0) put(1, 1);
   __syncthreads();
-  if (wave != 0) return;
-  add(0);
+  if (wave >= 2) return;
+  const int my_part = wave;  // wave 0 finishes the first half, wave 1 the second
+  if (wave == 0) add(0, 0);
+  if (wave == 1) add(1, 1);
 
   // ---- partial tile, layout of the tiled kernel: part[split][p][Qld], q = (r*3 + s)*C + c ----
   float *part = p.part + (long long)blockIdx.z * p.P * p.Qld;
   if (c < p.C) {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int gt = 0; gt < NGT; ++gt) {
+      if (!in_part(gt, my_part)) continue;
+      const int g = gt / 9, r = (gt % 9) / 3, sx = gt % 3;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int pr = pbase + g + G * e;
         if (pr >= p.P) continue;
-#pragma unroll
-        for (int r = 0; r < 3; ++r)
-#pragma unroll
-          for (int s = 0; s < 3; ++s) {
-            float *dst = part + (long long)pr * p.Qld + (r * 3 + s) * p.C + c;
-            if constexpr (V == 4) {
-              *reinterpret_cast<float4 *>(dst) =
-                  make_float4(acc[g][r][s][0][e], acc[g][r][s][1][e], acc[g][r][s][2][e], acc[g][r][s][3][e]);
-            } else if constexpr (V == 2) {
-              *reinterpret_cast<float2 *>(dst) = make_float2(acc[g][r][s][0][e], acc[g][r][s][1][e]);
-            } else {
-              dst[0] = acc[g][r][s][0][e];
-            }
-          }
+        float *dst = part + (long long)pr * p.Qld + (r * 3 + sx) * p.C + c;
+        if constexpr (V == 4) {
+          *reinterpret_cast<float4 *>(dst) =
+              make_float4(acc[g][r][sx][0][e], acc[g][r][sx][1][e], acc[g][r][sx][2][e], acc[g][r][sx][3][e]);
+        } else if constexpr (V == 2) {
+          *reinterpret_cast<float2 *>(dst) = make_float2(acc[g][r][sx][0][e], acc[g][r][sx][1][e]);
+        } else {
+          dst[0] = acc[g][r][sx][0][e];
+        }
       }
+    }
   }
+  if (wave != 0) return;
   // bias-gradient partials (channel chunk 0 only): lanes 0..3 hold the four rows of each group
   if (blockIdx.x == 0 && p.part_b && lane < 4) {
 #pragma unroll
@@ -252,7 +263,8 @@ inline SmallShape small_shape(int P, int C) {
 }  // namespace
 
 bool igemm_wgrad_small_applicable(const WgradProblem &p) {
-  const long long lim = 0x7FFFFFF0ll, B = p.M / ((long long)p.Ho * p.Wo);
+  // operands below 1 GiB: the kernel marks "no data" with bit 30 of a byte offset
+  const long long lim = 0x3FFFFFF0ll, B = p.M / ((long long)p.Ho * p.Wo);
   if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1 || p.Cs != 0) return false;
   // measured: from 32 output channels on the tiled MFMA kernel is faster (no padding left to save)
   if (p.Ho != p.H || p.Wo != p.W || p.P > 16 || p.P % 4 || p.C % 4) return false;
@@ -266,7 +278,7 @@ int igemm_wgrad_small_splits(int P, int C, int B, int H) {
   const SmallShape sh = small_shape(P, C);
   const int chunks = ((C + 64 * sh.V - 1) / (64 * sh.V)) * ((P + 4 * sh.G - 1) / (4 * sh.G));
   const int rows = B * H;
-  int S = 256 / (chunks > 0 ? chunks : 1);  // one workgroup per CU
+  int S = 256 / (chunks > 0 ? chunks : 1);  // one workgroup per CU (measured: 128 and 512 are slower)
   if (S > rows / 4) S = rows / 4;
   return S > 1 ? S : 1;
 }
