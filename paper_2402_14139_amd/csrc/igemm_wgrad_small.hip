@@ -117,13 +117,15 @@ __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, Sma
 
   int cur_e = 0;  // load cursor (uniform)
   float xr[RING][3][V], dr[RING][G];
+  int4 dsc_next;  // descriptor of element cur_e, read one step before its loads are issued
   auto load_elem = [&](int slot) {
-    const int4 dsc = desc[wave][cur_e & 127];  // same address in every lane
+    const int4 dsc = dsc_next;
     VLoad<V>::ld(rsx, dsc.x + lane_xo, xr[slot][0]);
     VLoad<V>::ld(rsx, dsc.y + lane_xo, xr[slot][1]);
     VLoad<V>::ld(rsx, dsc.z + lane_xo, xr[slot][2]);
     VLoad<G>::ld(rsd, dsc.w + lane_do, dr[slot]);
     ++cur_e;
+    dsc_next = desc[wave][cur_e & 127];  // same address in every lane
   };
 
   floatx4 acc[G][3][3][V];
@@ -141,6 +143,7 @@ __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, Sma
 
   // prologue: descriptors of the first 64 elements, then elements 0 .. RING-2
   make_desc(0);
+  dsc_next = desc[wave][0];
 #pragma unroll
   for (int i = 0; i + 1 < RING; ++i) load_elem(i);
 
@@ -166,6 +169,9 @@ __global__ __launch_bounds__(256, 1) void wgrad_small_kernel(WgradProblem p, Sma
                 acc[g][r][s][v] =
                     __builtin_amdgcn_mfma_f32_4x4x1f32(a, xr[(i + s) % RING][r][v], acc[g][r][s][v], 0, 0, 0);
         }
+        // nothing moves across a step boundary: left alone, the scheduler sinks the loads of a
+        // whole ring round behind ~180 MFMAs and the round then starts with a wait for all of them
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
