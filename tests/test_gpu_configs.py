@@ -1,8 +1,8 @@
 """GPU parity on the benchmark configurations' own layer shapes.
 
 * the ResNet-18-style configuration at FULL block batch sizes (64/128/256/512), i.e. in the
-  launch configuration bench.py times: one layer of each kind (stem, identity shortcut,
-  projection shortcut, stride-2, widest), whole local step against the oracle;
+  launch configuration bench.py times: every one of its 17 layers, whole local step against
+  the oracle;
 * every layer of the VGG-11-style configuration and sampled layers of the VGG-16- and
   ResNet-34-style ones at a reduced batch (the oracle is a plain loop nest).
 """
@@ -23,7 +23,7 @@ def _run(cfg_name, li, B, steps=1):
     G.check_step_results(f"{cfg_name}[{li}]", out, final)
 
 
-@pytest.mark.parametrize("li", [0, 2, 6, 9, 13, 16])
+@pytest.mark.parametrize("li", list(range(17)))
 def test_cfg3_full_batch(li):
     cfg = workloads.config("cfg3")
     _run("cfg3", li, cfg.blocks[cfg.layers[li].block].batch)
@@ -32,6 +32,13 @@ def test_cfg3_full_batch(li):
 @pytest.mark.parametrize("li", list(range(8)))
 def test_cfg2_all_layers_small_batch(li):
     _run("cfg2", li, 8, steps=2)
+
+
+@pytest.mark.parametrize("li", [5, 7])
+def test_cfg2_late_layers_full_batch(li):
+    """2x2 .. 4x4 maps at batch 128: few output tiles, so the forward, the head's convolution and
+    the data gradient all run with a split reduction."""
+    _run("cfg2", li, 128)
 
 
 @pytest.mark.parametrize("li", [0, 1, 3, 6, 9, 12])
