@@ -53,6 +53,28 @@ def test_out_dims_and_workspace(L):
     assert nf.nf_workspace_bytes(_layer(), _aux(), 8) > full
 
 
+@pytest.mark.parametrize("cfg_name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_workspace_of_every_benchmark_layer(L, cfg_name):
+    """Host-side sizing only: the workspace of every layer of every configuration holds at least
+    the tensors the step keeps there (dL/dZ, U, dU), its named regions lie inside it, and it
+    stays far below the 288 GB of the device."""
+    import workloads
+    cfg = workloads.config(cfg_name)
+    for ls in cfg.layers:
+        B = cfg.blocks[ls.block].batch
+        d, a = nf.LayerDesc(**ls.layer_desc_fields()), nf.AuxDesc(**ls.aux_desc_fields(cfg.n_classes))
+        total = nf.nf_workspace_bytes(d, a, B)
+        conv_out = 4 * B * ls.Ho * ls.Wo * ls.C_out
+        u = 4 * B * ls.Hp * ls.Wp * ls.A
+        assert conv_out + 2 * u <= total < (8 << 30), (cfg_name, ls.name, total)
+        for which in (nf.NF_WS_AUX_ACT, nf.NF_WS_POOL_ARG):
+            off, nbytes = nf.nf_workspace_region(d, a, B, which)
+            assert off % 256 == 0 and off + nbytes <= total
+        off, nbytes = nf.nf_workspace_region(d, a, B, nf.NF_WS_AUX_ACT)
+        assert nbytes == u
+        assert nf.nf_workspace_bytes(d, None, B) <= total
+
+
 @pytest.mark.parametrize("desc,status", [
     (dict(C_in=0), nf.NF_ERR_BAD_DESC),
     (dict(H_in=1, W_in=1, pad=0), nf.NF_ERR_BAD_DESC),          # filter larger than padded input
