@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 # scaled by what the same counter reads for a plain 1 GiB copy (`--traffic-calib`): FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0.  Averages over the launches of one step; summary under profiles/.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("cfg3_resnet18", "igemm_wgrad_fast_128x128"): 62.7e6 + 37.9e6,
-    ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 47.9e6 + 16.8e6,
+    ("cfg3_resnet18", "igemm_wgrad_fast_128x128"): 66.5e6 + 37.9e6,
+    ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 67.4e6 + 16.8e6,
 }
 
 
