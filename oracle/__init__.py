@@ -3,8 +3,13 @@
 Only tests, the smoke check and the bench's ``cpu_baseline`` leg may import this module.
 It shares nothing with the GPU library: logical NCHW / OIHW numpy arrays in, numpy out.
 
-Paper: Eq. 1 (layer), Eq. 2 (auxiliary head), Eq. 3 (loss), Algorithm 2 (local step),
-and the activation cache between blocks.
+Paper: Eq. 1 (layer), Eq. 2 (auxiliary head), Eq. 3 (loss), Algorithm 2 (local step; its
+Worker loop over the batches and layers of a block), and the activation cache between blocks
+(written by a forward-only sweep once a block is trained, read at the next block's batch size).
+
+The block-level functions at the end are plain Python loops over the single-layer calls; they
+are pinned by per-layer torch.optim.SGD / autograd runs of the same block and by the
+equivalence "training from the cache == training on recomputed activations".
 """
 from __future__ import annotations
 
@@ -225,3 +230,55 @@ def local_step(d: LayerDesc, a: AuxDesc, x, x_skip, labels, params: dict, mom: d
         *[_p(mom.get(k)) for k in PARAM_NAMES],
         C.c_double(lr), C.c_double(mu), _p(Y), C.byref(loss))
     return Y, float(loss.value), grads
+
+
+# ---- a block of consecutive local layers: the Worker loop of Algorithm 2 and the cache sweep ----
+@dataclass
+class BlockLayer:
+    """One local layer inside a block.  ``skip_src`` is -1, or the position (inside the block)
+    of the layer whose INPUT is this layer's shortcut tensor (0 = the block's input batch)."""
+    d: LayerDesc
+    a: AuxDesc
+    params: dict
+    mom: dict | None = None
+    skip_src: int = -1
+
+
+def _batches(n_items: int, B: int):
+    return [(f, min(B, n_items - f)) for f in range(0, n_items, B)]
+
+
+def block_train_epoch(layers, cache, cache_labels, idx, n_items, B, sample_shape, lr, mu):
+    """One pass of a block over ``n_items`` cached samples in batches of ``B`` (the last batch
+    may be smaller): for every batch, read it from the cache (rows ``idx[j]``, or the contiguous
+    rows when ``idx`` is None), then run the Algorithm 2 body layer by layer — each layer is
+    updated from its own local loss and hands on the activations it computed BEFORE its update.
+
+    Parameters and momentum buffers of ``layers`` are updated in place.  Returns the losses as
+    an array [n_batches, n_layers]."""
+    bl = _batches(n_items, B)
+    losses = np.zeros((len(bl), len(layers)), np.float64)
+    for j, (first, nb) in enumerate(bl):
+        sel = None if idx is None else np.asarray(idx[first:first + nb], np.int64)
+        x0, lab = cache_read(cache, cache_labels, first, sel, nb, sample_shape)
+        inputs = [x0]
+        for n, L in enumerate(layers):
+            xs = None if L.skip_src < 0 else inputs[L.skip_src]
+            y, loss, _ = local_step(L.d, L.a, inputs[n], xs, lab, L.params, L.mom, lr, mu)
+            losses[j, n] = loss
+            inputs.append(y)
+    return losses
+
+
+def block_fill_cache(layers, cache_in, labels_in, n_items, B, sample_shape, cache_out, labels_out):
+    """After a block has been trained: forward-only sweep with its final weights over the
+    block's input set (contiguous batches of ``B``, last one partial), storing the last layer's
+    emitted activations and the labels as rows ``[0, n_items)`` of the next cache."""
+    for first, nb in _batches(n_items, B):
+        x0, lab = cache_read(cache_in, labels_in, first, None, nb, sample_shape)
+        inputs = [x0]
+        for n, L in enumerate(layers):
+            xs = None if L.skip_src < 0 else inputs[L.skip_src]
+            p = L.params
+            inputs.append(layer_fwd(L.d, inputs[n], xs, p["W"], p["b"], p.get("Wp")).Y)
+        cache_write(cache_out, labels_out, first, inputs[-1], lab)

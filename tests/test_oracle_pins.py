@@ -441,3 +441,126 @@ def test_decision_overrides(oracle):
     mu[tuple(on)] = False  # switch one active aux unit off
     g3 = o.local_bwd(d, a, x, xs, lf, af, p["Wa"], p["Wf"], mask_u=mu, mask_z=lf.Z > 0)
     assert not np.array_equal(g3["Wa"], g["Wa"]) and np.array_equal(g3["Wf"], g["Wf"])
+
+
+# ---- a block of layers: Worker loop of Algorithm 2, cache sweep ------------------------------
+def _block(o, kind, Cls=3, dtype=np.float64, seed=11):
+    """Three local layers in a row.  'basic': plain conv with max-pool, then a basic block whose
+    second conv adds the basic block's input; 'proj': a stride-2 basic block with a 1x1 projection
+    shortcut from the block's input, then a plain conv."""
+    if kind == "basic":
+        specs = [workloads.LayerSpec("l0", 2, 8, 8, 4, A=2, pool_kind=1, pool_k=2, pool_stride=2),
+                 workloads.LayerSpec("l1", 4, 4, 4, 4, A=3),
+                 workloads.LayerSpec("l2", 4, 4, 4, 4, A=2, skip_kind=1, skip_C=4, skip_H=4, skip_W=4, skip_stride=1)]
+        skip_src = [-1, -1, 1]
+    else:
+        specs = [workloads.LayerSpec("l0", 2, 6, 6, 4, A=2, stride=2),
+                 workloads.LayerSpec("l1", 4, 3, 3, 4, A=2, skip_kind=2, skip_C=2, skip_H=6, skip_W=6, skip_stride=2),
+                 workloads.LayerSpec("l2", 4, 3, 3, 3, A=2)]
+        skip_src = [-1, 0, -1]
+    layers = []
+    for n, ls in enumerate(specs):
+        d = o.layer_desc(**ls.layer_desc_fields())
+        a = o.aux_desc(**ls.aux_desc_fields(Cls))
+        p = workloads.gen_layer_params(seed, n, ls, Cls, dtype=dtype, bias_std=0.3)
+        layers.append((d, a, p, skip_src[n]))
+    return specs, layers
+
+
+def _as_block_layers(o, layers, mu):
+    out = []
+    for d, a, p, s in layers:
+        pc = {k: (None if v is None else v.copy()) for k, v in p.items()}
+        mom = {k: (None if v is None else np.zeros_like(v)) for k, v in p.items()} if mu else None
+        out.append(o.BlockLayer(d, a, pc, mom, s))
+    return out
+
+
+@pytest.mark.parametrize("kind", ["basic", "proj"])
+@pytest.mark.parametrize("mu", [0.0, 0.9])
+def test_block_epoch_matches_torch_autograd(oracle, kind, mu):
+    """Three layers, shuffled order, partial last batch, two passes (so momentum and the updated
+    weights matter): losses, final weights and momentum buffers against per-layer torch.optim.SGD."""
+    o = oracle
+    specs, layers = _block(o, kind)
+    N, B, Cls = 7, 3, 3
+    g = workloads.rng_for(3, "block-pin", kind)
+    X = g.standard_normal((N, specs[0].C_in, specs[0].H_in, specs[0].W_in))
+    lab = g.integers(0, Cls, size=(N,)).astype(np.int32)
+    idx = g.permutation(N).astype(np.int64)
+    bl = _as_block_layers(o, layers, mu)
+    shape = X.shape[1:]
+    cache = X.reshape(N, -1).copy()
+    got = [o.block_train_epoch(bl, cache, lab, idx, N, B, shape, 0.05, mu) for _ in range(2)]
+    batches = [idx[f:f + B] for f in range(0, N, B)]
+    ref_losses, ref_final, ref_mom = torch_ref.block_epoch(layers, X, lab, batches * 2, 0.05, mu)
+    np.testing.assert_allclose(np.concatenate(got), np.array(ref_losses), rtol=1e-10, atol=1e-12)
+    for L, pf, mf in zip(bl, ref_final, ref_mom):
+        for k, v in pf.items():
+            np.testing.assert_allclose(L.params[k], v, rtol=1e-9, atol=1e-12, err_msg=k)
+            if mu:
+                np.testing.assert_allclose(L.mom[k], mf[k], rtol=1e-9, atol=1e-12, err_msg="v_" + k)
+
+
+@pytest.mark.parametrize("kind", ["basic", "proj"])
+def test_block_fill_cache_and_training_from_it(oracle, kind):
+    """The sweep stores exactly the composed forward of the block (torch, float64); training the
+    next block from that cache equals training it on activations recomputed from the raw inputs."""
+    o = oracle
+    specs, layers = _block(o, kind)
+    N, Cls = 7, 3
+    g = workloads.rng_for(4, "block-fill", kind)
+    X = g.standard_normal((N, specs[0].C_in, specs[0].H_in, specs[0].W_in))
+    lab = g.integers(0, Cls, size=(N,)).astype(np.int32)
+    bl = _as_block_layers(o, layers, 0.0)
+    last = specs[-1]
+    out_shape = (last.C_out, last.Hp, last.Wp)
+    cache_out = np.full((N, int(np.prod(out_shape))), np.nan)
+    lab_out = np.full((N,), -1, np.int32)
+    o.block_fill_cache(bl, X.reshape(N, -1).copy(), lab, N, 3, X.shape[1:], cache_out, lab_out)
+    ref = torch_ref.block_forward(layers, X)
+    np.testing.assert_allclose(cache_out.reshape(ref.shape), ref, rtol=1e-11, atol=1e-13)
+    assert np.array_equal(lab_out, lab)
+    # a one-layer second block, trained (a) from the cache, (b) from the recomputed activations
+    nxt = workloads.LayerSpec("n", last.C_out, last.Hp, last.Wp, 3, A=2)
+    d, a = o.layer_desc(**nxt.layer_desc_fields()), o.aux_desc(**nxt.aux_desc_fields(Cls))
+    p = workloads.gen_layer_params(12, 0, nxt, Cls, dtype=np.float64, bias_std=0.3)
+    idx = g.permutation(N).astype(np.int64)
+    runs = []
+    for src in (cache_out, ref.reshape(N, -1).copy()):
+        blk = _as_block_layers(o, [(d, a, p, -1)], 0.9)
+        losses = o.block_train_epoch(blk, src, lab_out, idx, N, 4, out_shape, 0.05, 0.9)
+        runs.append((losses, blk[0].params))
+    np.testing.assert_allclose(runs[0][0], runs[1][0], rtol=1e-9)
+    for k, v in runs[0][1].items():
+        if v is not None:
+            np.testing.assert_allclose(v, runs[1][1][k], rtol=1e-8, atol=1e-12)
+
+
+def test_block_epoch_is_the_sequence_of_local_steps(oracle):
+    """Locality across layers: a layer's update inside the block pass depends only on its own
+    input batch — perturbing layer 2's parameters leaves layer 0's and 1's results untouched,
+    and the tensor handed on is the one computed with the pre-update weights."""
+    o = oracle
+    specs, layers = _block(o, "basic")
+    N, Cls = 4, 3
+    g = workloads.rng_for(5, "block-local")
+    X = g.standard_normal((N, 2, 8, 8))
+    lab = g.integers(0, Cls, size=(N,)).astype(np.int32)
+    a_run = _as_block_layers(o, layers, 0.0)
+    b_run = _as_block_layers(o, layers, 0.0)
+    b_run[2].params["W"] += 0.5
+    la = o.block_train_epoch(a_run, X.reshape(N, -1).copy(), lab, None, N, 4, X.shape[1:], 0.1, 0.0)
+    lb = o.block_train_epoch(b_run, X.reshape(N, -1).copy(), lab, None, N, 4, X.shape[1:], 0.1, 0.0)
+    assert np.array_equal(la[:, :2], lb[:, :2]) and la[0, 2] != lb[0, 2]
+    for n in (0, 1):
+        for k, v in a_run[n].params.items():
+            assert v is None or np.array_equal(v, b_run[n].params[k])
+    # pre-update hand-over: layer 1's first loss equals the head loss on layer 0's output under
+    # layer 0's ORIGINAL weights
+    d0, a0, p0, _ = layers[0]
+    d1, a1, p1, _ = layers[1]
+    y0 = o.layer_fwd(d0, X, None, p0["W"], p0["b"]).Y
+    y1 = o.layer_fwd(d1, y0, None, p1["W"], p1["b"]).Y
+    want = o.aux_fwd_loss(a1, y1, lab, p1["Wa"], p1["ba"], p1["Wf"], p1["bf"]).loss
+    assert abs(la[0, 1] - want) < 1e-12
