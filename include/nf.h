@@ -157,6 +157,58 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
                       const nf_aux_params *ga, const nf_layer_params *vp, const nf_aux_params *va,
                       float *y_out, float *loss_out, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- a block of consecutive local layers (the paper's partition of the network into blocks,
+ * each trained at its own batch size; Worker loop of Algorithm 2; "Efficient Forward Propagation
+ * via Prefetching and Adaptive Batching") ---------------------------------------------------------
+ * All arrays are HOST arrays with n_layers entries; the pointers inside the parameter structs
+ * are device pointers.  Layer n+1 reads what layer n emits, so its C_in/H_in/W_in must equal
+ * layer n's C_out/Hp/Wp.  skip_src (NULL = no shortcuts) gives per layer -1, or the position
+ * m <= n of the layer whose INPUT tensor is layer n's shortcut (0 = the block's input batch);
+ * that tensor's shape must equal the layer's skip_C/skip_H/skip_W.  aux/ap/gp/ga are not read by
+ * nf_block_fill_cache and may be NULL there; vp/va may be NULL when momentum == 0.  gp/ga are
+ * scratch of the pass (they hold the last batch's gradients afterwards). */
+typedef struct {
+  int32_t n_layers;
+  const nf_layer_desc *layers;
+  const nf_aux_desc *aux;
+  const int32_t *skip_src;
+  const nf_layer_params *p;
+  const nf_aux_params *ap;
+  const nf_layer_params *gp;
+  const nf_aux_params *ga;
+  const nf_layer_params *vp;
+  const nf_aux_params *va;
+} nf_block;
+
+/* Workspace of the two block calls at batch size B: two input batches (double buffer), every
+ * layer's emitted batch, and the largest single-layer workspace. */
+int32_t nf_block_workspace_bytes(const nf_block *blk, int32_t B, size_t *out);
+
+/* One pass of the block over n_items cached samples in batches of B (the last one may be
+ * smaller): per batch, nf_cache_read (rows idx[j], device int64 [n_items], or rows 0..n_items-1
+ * when idx == NULL; cache [capacity][C_in*H_in*W_in of layer 0], cache_labels [capacity]), then
+ * nf_local_step layer by layer, each layer handing on the activations it emitted BEFORE its
+ * update.  losses (device, [ceil(n_items/B)][n_layers]) receives every local loss.
+ * prefetch_stream != NULL: the read of batch j+1 is enqueued there and overlaps the training of
+ * batch j (the paper's prefetching); it is ordered after everything already enqueued on `stream`
+ * and joined back into `stream` before the call's last batch, so `stream` alone orders the
+ * result.  That mode uses four process-wide HIP events per device, created on first use: calls
+ * with a prefetch stream must not overlap in time on one device.  Both streams must have the
+ * default priority. */
+int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t B, int64_t n_items,
+                             const float *cache, const int32_t *cache_labels, int64_t capacity,
+                             const int64_t *idx, float *losses, void *ws, size_t ws_bytes,
+                             void *stream, void *prefetch_stream);
+
+/* After the block is trained: forward-only sweep with its final weights over rows [0, n_items)
+ * of its input cache in batches of B (last one partial), writing the last layer's emitted
+ * activations and the labels to rows [0, n_items) of the next block's cache
+ * (cache_out [capacity_out][C_out*Hp*Wp of the last layer]). */
+int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, const float *cache_in,
+                            const int32_t *labels_in, int64_t capacity_in, float *cache_out,
+                            int32_t *labels_out, int64_t capacity_out, void *ws, size_t ws_bytes,
+                            void *stream);
+
 /* ---- measurement aid (not a step of the method) ---------------------------------------------
  * Between nf_prof_begin and nf_prof_end every kernel the library enqueues is bracketed by a
  * HIP-event pair on the caller's stream.  nf_prof_end waits for those events (the only call

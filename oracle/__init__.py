@@ -248,14 +248,16 @@ def _batches(n_items: int, B: int):
     return [(f, min(B, n_items - f)) for f in range(0, n_items, B)]
 
 
-def block_train_epoch(layers, cache, cache_labels, idx, n_items, B, sample_shape, lr, mu):
+def block_train_epoch(layers, cache, cache_labels, idx, n_items, B, sample_shape, lr, mu, step=None):
     """One pass of a block over ``n_items`` cached samples in batches of ``B`` (the last batch
     may be smaller): for every batch, read it from the cache (rows ``idx[j]``, or the contiguous
     rows when ``idx`` is None), then run the Algorithm 2 body layer by layer — each layer is
     updated from its own local loss and hands on the activations it computed BEFORE its update.
 
     Parameters and momentum buffers of ``layers`` are updated in place.  Returns the losses as
-    an array [n_batches, n_layers]."""
+    an array [n_batches, n_layers].  ``step(j, n, L, x, x_skip, labels) -> (y, loss)``, if given,
+    stands in for ``local_step`` on layer ``L`` (a GPU comparison uses it to run the same step with
+    the ReLU / max-pool decisions that are ties within rounding taken as the kernels took them)."""
     bl = _batches(n_items, B)
     losses = np.zeros((len(bl), len(layers)), np.float64)
     for j, (first, nb) in enumerate(bl):
@@ -264,7 +266,10 @@ def block_train_epoch(layers, cache, cache_labels, idx, n_items, B, sample_shape
         inputs = [x0]
         for n, L in enumerate(layers):
             xs = None if L.skip_src < 0 else inputs[L.skip_src]
-            y, loss, _ = local_step(L.d, L.a, inputs[n], xs, lab, L.params, L.mom, lr, mu)
+            if step is not None:
+                y, loss = step(j, n, L, inputs[n], xs, lab)
+            else:
+                y, loss, _ = local_step(L.d, L.a, inputs[n], xs, lab, L.params, L.mom, lr, mu)
             losses[j, n] = loss
             inputs.append(y)
     return losses

@@ -19,7 +19,8 @@ NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE
 
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
-           "nf_prof_begin", "nf_prof_end", "nf_workspace_region")
+           "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
+           "nf_block_train_epoch", "nf_block_fill_cache")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG = 0, 1
 
@@ -57,6 +58,14 @@ class ProfRecord(C.Structure):
 
 class AuxParams(C.Structure):
     _fields_ = [("Wa", C.c_void_p), ("ba", C.c_void_p), ("Wf", C.c_void_p), ("bf", C.c_void_p)]
+
+
+class Block(C.Structure):
+    """nf_block: host arrays of n_layers descriptors / parameter structs."""
+    _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(LayerDesc)), ("aux", C.POINTER(AuxDesc)),
+                ("skip_src", C.POINTER(C.c_int32)), ("p", C.POINTER(LayerParams)), ("ap", C.POINTER(AuxParams)),
+                ("gp", C.POINTER(LayerParams)), ("ga", C.POINTER(AuxParams)), ("vp", C.POINTER(LayerParams)),
+                ("va", C.POINTER(AuxParams))]
 
 
 _lib = None
@@ -98,6 +107,12 @@ def lib():
         L.nf_prof_end.argtypes = [C.POINTER(ProfRecord), C.c_int32, C.POINTER(C.c_int32)]
         L.nf_workspace_region.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
                                           C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.nf_block_workspace_bytes.argtypes = [C.POINTER(Block), C.c_int32, C.POINTER(C.c_size_t)]
+        L.nf_block_train_epoch.argtypes = [C.POINTER(Block), C.POINTER(SgdDesc), C.c_int32, C.c_int64, C.c_void_p,
+                                           C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                           C.c_void_p, C.c_void_p]
+        L.nf_block_fill_cache.argtypes = [C.POINTER(Block), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -222,3 +237,53 @@ def nf_prof_end(cap: int = 64):
     _check(lib().nf_prof_end(recs, cap, C.byref(n)), "nf_prof_end")
     return [dict(kernel=recs[i].kernel.decode(), launches=int(recs[i].launches), ms=float(recs[i].ms),
                  flops=float(recs[i].flops), bytes=float(recs[i].bytes)) for i in range(min(n.value, cap))]
+
+
+def make_block(descs, auxs, skip_src, p, ap, gp=None, ga=None, vp=None, va=None) -> Block:
+    """Packs per-layer descriptor / parameter structs (lists) into an nf_block.  The arrays are
+    kept alive as attributes of the returned struct."""
+    n = len(descs)
+    blk = Block()
+    blk.n_layers = n
+
+    def arr(ctype, items):
+        if items is None:
+            return None
+        a = (ctype * n)()
+        for i, it in enumerate(items):
+            C.memmove(C.byref(a, i * C.sizeof(ctype)), C.byref(it), C.sizeof(ctype))
+        return a
+
+    keep = dict(layers=arr(LayerDesc, descs), aux=arr(AuxDesc, auxs),
+                skip_src=None if skip_src is None else (C.c_int32 * n)(*skip_src),
+                p=arr(LayerParams, p), ap=arr(AuxParams, ap), gp=arr(LayerParams, gp), ga=arr(AuxParams, ga),
+                vp=arr(LayerParams, vp), va=arr(AuxParams, va))
+    for k, v in keep.items():
+        if v is not None:
+            setattr(blk, k, v)
+    blk._keep = keep
+    return blk
+
+
+def nf_block_workspace_bytes(blk: Block, B: int) -> int:
+    out = C.c_size_t()
+    _check(lib().nf_block_workspace_bytes(C.byref(blk), B, C.byref(out)), "nf_block_workspace_bytes")
+    return int(out.value)
+
+
+def nf_block_train_epoch(blk: Block, lr, momentum, B, n_items, cache, cache_labels, capacity, idx, losses, ws,
+                         stream=None, prefetch_stream=None):
+    s = SgdDesc(lr, momentum)
+    wp, wn = _ws(ws)
+    _check(lib().nf_block_train_epoch(C.byref(blk), C.byref(s), B, n_items, _ptr(cache), _ptr(cache_labels), capacity,
+                                      _ptr(idx), _ptr(losses), wp, wn, _stream(stream),
+                                      None if prefetch_stream is None else _stream(prefetch_stream)),
+           "nf_block_train_epoch")
+
+
+def nf_block_fill_cache(blk: Block, B, n_items, cache_in, labels_in, capacity_in, cache_out, labels_out,
+                        capacity_out, ws, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().nf_block_fill_cache(C.byref(blk), B, n_items, _ptr(cache_in), _ptr(labels_in), capacity_in,
+                                     _ptr(cache_out), _ptr(labels_out), capacity_out, wp, wn, _stream(stream)),
+           "nf_block_fill_cache")

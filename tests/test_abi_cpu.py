@@ -152,3 +152,95 @@ def test_strerror(L):
     for code in range(-6, 0):
         assert nf.strerror(code) and nf.strerror(code) != "unknown status"
     assert nf.strerror(-99) == "unknown status"
+
+
+# ---- block-level calls: everything below fails (or only sizes things) before any enqueue ----------
+def _cfg_block(cfg_name, k, good=0x10000, with_mom=True):
+    import workloads
+    cfg = workloads.config(cfg_name)
+    b = cfg.blocks[k]
+    specs = [cfg.layers[i] for i in b.layers]
+    descs = [nf.LayerDesc(**ls.layer_desc_fields()) for ls in specs]
+    auxs = [nf.AuxDesc(**ls.aux_desc_fields(cfg.n_classes)) for ls in specs]
+    skip = [(-1 if not ls.skip_kind else ls.skip_src - b.layers[0]) for ls in specs]
+    lp = [nf.LayerParams(good, good, good if ls.skip_kind == 2 else None) for ls in specs]
+    apar = [nf.AuxParams(good, good, good, good) for _ in specs]
+    blk = nf.make_block(descs, auxs, skip, lp, apar, lp, apar, lp if with_mom else None, apar if with_mom else None)
+    return cfg, b, specs, blk
+
+
+@pytest.mark.parametrize("cfg_name,k", [("cfg3", 0), ("cfg3", 3), ("cfg2", 0), ("cfg5", 0), ("cfg5", 2)])
+def test_block_workspace(L, cfg_name, k):
+    cfg, b, specs, blk = _cfg_block(cfg_name, k)
+    B = b.batch
+    total = nf.nf_block_workspace_bytes(blk, B)
+    up = lambda v: (v + 255) // 256 * 256  # noqa: E731
+    f = specs[0]
+    want = 2 * (up(4 * B * f.C_in * f.H_in * f.W_in) + up(4 * B))
+    want += sum(up(4 * B * ls.C_out * ls.Hp * ls.Wp) for ls in specs)
+    want += up(max(nf.nf_workspace_bytes(blk._keep["layers"][i], blk._keep["aux"][i], B) for i in range(len(specs))))
+    assert total == want and total < (16 << 30)
+
+
+def test_block_calls_validate_before_enqueue(L):
+    good = 0x10000
+    cfg, b, specs, blk = _cfg_block("cfg3", 1)
+    B, n = b.batch, len(specs)
+    need = nf.nf_block_workspace_bytes(blk, B)
+    s = nf.SgdDesc(0.01, 0.9)
+    out = C.c_size_t()
+
+    def train(blk_, sgd=s, n_items=4 * B, cap=8 * B, idx=None, ws=good << 8, ws_bytes=need, cache=good, lab=good,
+              losses=good, B_=B):
+        return L.nf_block_train_epoch(C.byref(blk_), C.byref(sgd), B_, n_items, cache, lab, cap, idx, losses, ws,
+                                      ws_bytes, None, None)
+
+    def fill(blk_, n_items=4 * B, cap_in=8 * B, cap_out=8 * B, ws_bytes=need, cin=good, cout=good):
+        return L.nf_block_fill_cache(C.byref(blk_), B, n_items, cin, good, cap_in, cout, good, cap_out, good << 8,
+                                     ws_bytes, None)
+
+    assert L.nf_block_workspace_bytes(None, B, C.byref(out)) == nf.NF_ERR_NULL
+    assert L.nf_block_workspace_bytes(C.byref(blk), B, None) == nf.NF_ERR_NULL
+    assert L.nf_block_workspace_bytes(C.byref(blk), 0, C.byref(out)) == nf.NF_ERR_BAD_DESC
+    # argument errors
+    assert train(blk, cache=None) == nf.NF_ERR_NULL
+    assert train(blk, losses=None) == nf.NF_ERR_NULL
+    assert train(blk, n_items=0) == nf.NF_ERR_BAD_DESC
+    assert train(blk, n_items=9 * B) == nf.NF_ERR_CACHE_RANGE          # contiguous rows beyond the cache
+    assert train(blk, ws_bytes=need - 1) == nf.NF_ERR_WORKSPACE
+    assert train(blk, ws=(good << 8) + 16) == nf.NF_ERR_WORKSPACE
+    assert train(blk, cache=good + 4) == nf.NF_ERR_BAD_DESC
+    assert fill(blk, n_items=9 * B) == nf.NF_ERR_CACHE_RANGE
+    assert fill(blk, cap_out=B) == nf.NF_ERR_CACHE_RANGE
+    assert fill(blk, ws_bytes=16) == nf.NF_ERR_WORKSPACE
+    assert fill(blk, cout=None) == nf.NF_ERR_NULL
+    # momentum without momentum buffers
+    _, _, _, nomom = _cfg_block("cfg3", 1, with_mom=False)
+    assert train(nomom) == nf.NF_ERR_NULL
+    # structure errors: broken chain, missing / wrong shortcut wiring, empty block, missing parameters
+    descs = [nf.LayerDesc(**ls.layer_desc_fields()) for ls in specs]
+    auxs = [nf.AuxDesc(**ls.aux_desc_fields(cfg.n_classes)) for ls in specs]
+    skip = [(-1 if not ls.skip_kind else ls.skip_src - b.layers[0]) for ls in specs]
+    lp = [nf.LayerParams(good, good, good) for _ in specs]
+    apar = [nf.AuxParams(good, good, good, good) for _ in specs]
+    chain = nf.make_block(descs[:1] + descs[2:], auxs[:1] + auxs[2:], None, lp[:-1], apar[:-1], lp[:-1], apar[:-1],
+                          lp[:-1], apar[:-1])
+    assert L.nf_block_workspace_bytes(C.byref(chain), B, C.byref(out)) == nf.NF_ERR_BAD_DESC
+    assert any(ls.skip_kind for ls in specs)
+    noskip = nf.make_block(descs, auxs, None, lp, apar, lp, apar, lp, apar)
+    assert train(noskip) == nf.NF_ERR_BAD_DESC
+    late = nf.make_block(descs, auxs, [n + 3 if v >= 0 else -1 for v in skip], lp, apar, lp, apar, lp, apar)
+    assert train(late) == nf.NF_ERR_BAD_DESC
+    wrong = nf.make_block(descs, auxs, [(v + 1 if v >= 0 and v + 1 <= i and specs[i].skip_kind == 2 else v)
+                                        for i, v in enumerate(skip)], lp, apar, lp, apar, lp, apar)
+    if [v for v in skip] != [wrong._keep["skip_src"][i] for i in range(n)]:
+        assert train(wrong) == nf.NF_ERR_BAD_DESC                         # projection source of another shape
+    empty = nf.make_block(descs, auxs, skip, lp, apar, lp, apar, lp, apar)
+    empty.n_layers = 0
+    assert train(empty) == nf.NF_ERR_BAD_DESC
+    nop = nf.make_block(descs, auxs, skip, [nf.LayerParams(good, None, good)] * n, apar, lp, apar, lp, apar)
+    assert train(nop) == nf.NF_ERR_NULL
+    assert fill(nop) == nf.NF_ERR_NULL
+    nohead = nf.make_block(descs, None, skip, lp, None)
+    assert train(nohead) == nf.NF_ERR_NULL
+    assert L.nf_block_workspace_bytes(C.byref(nohead), B, C.byref(out)) == nf.NF_OK and out.value < need
