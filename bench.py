@@ -271,6 +271,47 @@ def main():
         log(f"[layer] {li:2d} {ls.name:<8} blk{ls.block} B={B:<4d} {ms:8.3f} ms {B / (ms * 1e-3):10.0f} img/s "
             f"{fl / (ms * 1e-3) / 1e12:7.2f} TFLOP/s")
 
+    # ---- the same work through the block-level calls (Worker loop inside the library) ----------
+    # per block: nf_block_train_epoch over `steps` shuffled batches of its cache, without and with
+    # the prefetch stream (read of batch j+1 overlapping the training of batch j); then the
+    # forward-only sweep that fills the next block's cache over all N samples.
+    block_driver = None
+    if not args.no_prof:
+        main_s, side_s = torch.cuda.Stream(), torch.cuda.Stream()
+        tot = {"plain": 0.0, "prefetch": 0.0}
+        fill_ms, fill_bytes = 0.0, 0.0
+        for k, b in enumerate(cfg.blocks):
+            Ls = [layers[li] for li in b.layers]
+            skip = [(-1 if not cfg.layers[li].skip_kind else cfg.layers[li].skip_src - b.layers[0]) for li in b.layers]
+            mom = cfg.momentum != 0
+            blk = nf.make_block([l.d for l in Ls], [l.a for l in Ls], skip, [l.sp for l in Ls], [l.sa for l in Ls],
+                                [l.sgp for l in Ls], [l.sga for l in Ls], [l.svp for l in Ls] if mom else None,
+                                [l.sva for l in Ls] if mom else None)
+            bws = torch.empty(nf.nf_block_workspace_bytes(blk, b.batch), dtype=torch.uint8, device=dev)
+            nb = min(args.steps, N // b.batch)
+            bl = torch.zeros((nb, len(Ls)), dtype=torch.float32, device=dev)
+            torch.cuda.synchronize()
+            for mode, pf in (("plain", None), ("prefetch", side_s), ("plain", None), ("prefetch", side_s)):
+                t0 = time.perf_counter()
+                nf.nf_block_train_epoch(blk, cfg.lr, cfg.momentum, b.batch, nb * b.batch, caches[k], clabels[k], N,
+                                        perms[k], bl, bws, stream=main_s, prefetch_stream=pf)
+                main_s.synchronize()
+                tot[mode] += (time.perf_counter() - t0) * 1e3 / nb / 2
+            if k + 1 < nblk:
+                t0 = time.perf_counter()
+                nf.nf_block_fill_cache(blk, b.batch, N, caches[k], clabels[k], N, wcaches[k + 1], wlabels[k + 1], N,
+                                       bws, stream=main_s)
+                main_s.synchronize()
+                fill_ms += (time.perf_counter() - t0) * 1e3
+            del bws
+        block_driver = {"ms_per_step": round(tot["plain"], 4), "ms_per_step_prefetch": round(tot["prefetch"], 4),
+                        "note": "nf_block_train_epoch per block (no cache write inside a training pass), summed "
+                                "over blocks per batch; prefetch = cache read of the next batch on a second stream",
+                        "fill_cache_sweep_ms": round(fill_ms, 2),
+                        "fill_cache_images_per_s": round((nblk - 1) * N / (fill_ms * 1e-3), 1) if fill_ms else None}
+        log(f"[block] train pass {tot['plain']:.3f} ms/step, with prefetch {tot['prefetch']:.3f} ms/step; "
+            f"cache-fill sweeps of {nblk - 1} blocks x {N} samples {fill_ms:.1f} ms")
+
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -329,7 +370,8 @@ def main():
                    "gflop_per_step": round(flops_per_step / 1e9, 1)},
         "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
         "losses_finite": finite,
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "layers": per_layer,
+        "roofline": roofline, "cpu_baseline": cpu, "block_driver": block_driver, "kernels": kernels,
+        "layers": per_layer,
     }
     print(json.dumps(out), flush=True)
 
