@@ -49,3 +49,13 @@ def test_cfg4_sampled_layers_small_batch(li):
 @pytest.mark.parametrize("li", [0, 1, 8, 16, 32])
 def test_cfg5_sampled_layers_small_batch(li):
     _run("cfg5", li, 2)
+
+
+@pytest.mark.parametrize("cfg_name,li", [("cfg3_aan", 5), ("cfg3_aan", 6), ("cfg3_aan", 10), ("cfg3_aan", 16),
+                                         ("cfg3_ll256", 0), ("cfg3_ll256", 2)])
+def test_wide_heads_full_batch(cfg_name, li):
+    """The paper's own head widths (32 before the first down-sampling, 256 after; 256 everywhere
+    for classic local learning) on the ResNet-18-style network at full block batch: the head's
+    convolution, its weight gradient and its data gradient are then full-width MFMA GEMMs."""
+    cfg = workloads.config(cfg_name)
+    _run(cfg_name, li, cfg.blocks[cfg.layers[li].block].batch)

@@ -185,7 +185,35 @@ def _cfg5():
                   notes=_LR_NOTE.replace("lr 0.001", "lr 1e-5"), extra={"memory_budget_bytes": 16 << 30})
 
 
-_BUILDERS = {"cfg1": _cfg1, "cfg2": _cfg2, "cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}
+def _aan_rule(layers):
+    """The paper's own head widths (its "Adaptive Auxiliary Networks" rule): layers before the
+    first down-sampling get half the narrowest layer width, all later ones half the widest."""
+    lo, hi = min(l.C_out for l in layers) // 2, max(l.C_out for l in layers) // 2
+    first_down = next((i for i, l in enumerate(layers) if l.stride > 1 or l.pool_kind), len(layers))
+    for i, l in enumerate(layers):
+        l.A = lo if i < first_down else hi
+
+
+def _cfg3_aan():
+    """cfg3's network and blocks with the paper's head widths (32 for the stem and stage 1,
+    256 afterwards) instead of the benchmark configuration's 32/16/8/4: wide aux GEMMs."""
+    c = _cfg3()
+    _aan_rule(c.layers)
+    c.name = "cfg3_resnet18_aan_heads"
+    return c
+
+
+def _cfg3_ll256():
+    """cfg3's network with the fixed 256-filter heads of classic local learning."""
+    c = _cfg3()
+    for l in c.layers:
+        l.A = 256
+    c.name = "cfg3_resnet18_ll256_heads"
+    return c
+
+
+_BUILDERS = {"cfg1": _cfg1, "cfg2": _cfg2, "cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5,
+             "cfg3_aan": _cfg3_aan, "cfg3_ll256": _cfg3_ll256}
 
 
 def config_names():
