@@ -180,6 +180,92 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
   }
 }
 
+// The same step for wide heads (many pooled features): G samples per workgroup share every load
+// of Wf, and the workgroup has WT = 1024 threads so that the chip still holds as many wavefronts
+// as with one sample per 256 threads.  Logits: one wavefront per class, its lanes striding the
+// features (coalesced float4 reads of the class's row), wavefront sum; softmax: one wavefront per
+// sample; dPq: one thread per feature, the loop over classes unrolled so that many independent
+// loads are in flight.  Needs F % 4 == 0.  Dynamic LDS: G * (F + Cls) floats.
+constexpr int WT = 1024;
+template <int G>
+__global__ __launch_bounds__(WT) void head_fc_wide_kernel(HeadShape s, const float *__restrict__ Pq,
+                                                          const int32_t *__restrict__ labels,
+                                                          const float *__restrict__ Wf,
+                                                          const float *__restrict__ bf, float *__restrict__ dz,
+                                                          float *__restrict__ loss_n, float *__restrict__ dPq) {
+  extern __shared__ float sm[];
+  float *pq = sm;               // [G][F]
+  float *z = pq + G * s.F;      // [G][Cls]
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int n0 = blockIdx.x * G;
+  const int ng = min(G, s.B - n0);
+  for (int i = t * 4; i < G * s.F; i += WT * 4) {
+    const int g = i / s.F;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (g < ng) v = *reinterpret_cast<const float4 *>(Pq + (long long)n0 * s.F + i);
+    *reinterpret_cast<float4 *>(pq + i) = v;
+  }
+  __syncthreads();
+  for (int q = wave; q < s.Cls; q += WT / 64) {
+    const float *wr = Wf + (long long)q * s.F;
+    float acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) acc[g] = 0.f;
+#pragma unroll 4
+    for (int f = lane * 4; f < s.F; f += 256) {
+      const float4 w = *reinterpret_cast<const float4 *>(wr + f);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float4 x = *reinterpret_cast<const float4 *>(pq + g * s.F + f);
+        acc[g] += w.x * x.x + w.y * x.y + w.z * x.z + w.w * x.w;
+      }
+    }
+    const float bias = bf ? bf[q] : 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float v = wave_sum(acc[g]);
+      if (lane == 0) z[g * s.Cls + q] = v + bias;
+    }
+  }
+  __syncthreads();
+  const float invB = 1.f / (float)s.B;
+  if (wave < ng) {
+    const int g = wave;
+    float *zg = z + g * s.Cls;
+    float m = -INFINITY;
+    for (int q = lane; q < s.Cls; q += 64) m = fmaxf(m, zg[q]);
+    m = wave_max(m);
+    float se = 0.f;
+    for (int q = lane; q < s.Cls; q += 64) se += expf(zg[q] - m);
+    se = wave_sum(se);
+    const float lse = m + logf(se);
+    const int y = labels[n0 + g];
+    const float zy = (y >= 0 && y < s.Cls) ? zg[y] : 0.f;
+    // (one wavefront owns zg: its read of zg[y] above is issued before the stores below)
+    for (int q = lane; q < s.Cls; q += 64) {
+      const float d = (expf(zg[q] - lse) - (q == y ? 1.f : 0.f)) * invB;
+      dz[(long long)(n0 + g) * s.Cls + q] = d;
+      zg[q] = d;
+    }
+    if (lane == 0) loss_n[n0 + g] = lse - zy;
+  }
+  __syncthreads();
+  for (int f = t; f < s.F; f += WT) {
+    float acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) acc[g] = 0.f;
+#pragma unroll 20
+    for (int q = 0; q < s.Cls; ++q) {
+      const float w = Wf[(long long)q * s.F + f];
+#pragma unroll
+      for (int g = 0; g < G; ++g) acc[g] += z[g * s.Cls + q] * w;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (g < ng) dPq[(long long)(n0 + g) * s.F + f] = acc[g];
+  }
+}
+
 // batch mean of the per-sample losses, fixed order (one workgroup)
 __device__ inline void loss_mean_block(const float *__restrict__ loss_n, int B, float *__restrict__ out, float *red) {
   float acc = 0.f;
@@ -336,6 +422,13 @@ hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int
 
 hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
                           const float *bf, float *dz, float *loss_n, float *dPq, hipStream_t st) {
+  constexpr int G = 4;
+  const size_t lds_wide = (size_t)G * (h.F + h.Cls) * sizeof(float);
+  if (h.F >= 256 && h.F % 4 == 0 && lds_wide <= 48 * 1024) {
+    hipLaunchKernelGGL(head_fc_wide_kernel<G>, dim3((h.B + G - 1) / G), dim3(WT), lds_wide, st, h, Pq, labels, Wf, bf,
+                       dz, loss_n, dPq);
+    return hipGetLastError();
+  }
   const size_t lds = (size_t)(h.F + h.Cls + 8) * sizeof(float);
   hipLaunchKernelGGL(head_fc_kernel, dim3(h.B), dim3(HT), lds, st, h, Pq, labels, Wf, bf, dz, loss_n, dPq);
   return hipGetLastError();
