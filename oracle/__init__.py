@@ -44,7 +44,12 @@ class LayerDesc(C.Structure):
 
 class AuxDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
-        "C_in", "H_in", "W_in", "A", "R", "S", "pad", "relu", "pool_oh", "pool_ow", "n_classes")]
+        "C_in", "H_in", "W_in", "A", "R", "S", "pad", "relu", "pool_oh", "pool_ow", "n_classes",
+        "head_pool", "loss_kind")]
+
+
+HEAD_POOL_AVG, HEAD_POOL_MAX = 0, 1
+LOSS_CE, LOSS_MSE = 0, 1
 
 
 def lib():
@@ -89,8 +94,9 @@ def layer_desc(C_in, H_in, W_in, C_out, R=3, S=3, stride=1, pad=1, pool_kind=0, 
                      pool_pad, skip_kind, skip_C, skip_H, skip_W, skip_stride)
 
 
-def aux_desc(C_in, H_in, W_in, A, n_classes, R=3, S=3, pad=1, relu=1, pool_oh=2, pool_ow=2) -> AuxDesc:
-    return AuxDesc(C_in, H_in, W_in, A, R, S, pad, relu, pool_oh, pool_ow, n_classes)
+def aux_desc(C_in, H_in, W_in, A, n_classes, R=3, S=3, pad=1, relu=1, pool_oh=2, pool_ow=2, head_pool=0,
+             loss_kind=0) -> AuxDesc:
+    return AuxDesc(C_in, H_in, W_in, A, R, S, pad, relu, pool_oh, pool_ow, n_classes, head_pool, loss_kind)
 
 
 def layer_dims(d: LayerDesc):
@@ -134,10 +140,11 @@ class AuxFwd:
     loss: float
     dz: np.ndarray
     Upre: np.ndarray | None = None
+    parg: np.ndarray | None = None
 
 
 def aux_fwd_loss(a: AuxDesc, y, labels, Wa, ba, Wf, bf) -> AuxFwd:
-    """Eq. 2 and Eq. 3 (cross-entropy, batch mean) for the emitted activations ``y``."""
+    """Eq. 2 and Eq. 3 (batch mean of the head's loss) for the emitted activations ``y``."""
     dt = y.dtype
     B = y.shape[0]
     Hu, Wu = aux_out_hw(a)
@@ -146,18 +153,21 @@ def aux_fwd_loss(a: AuxDesc, y, labels, Wa, ba, Wf, bf) -> AuxFwd:
     z = np.empty((B, a.n_classes), dt)
     dz = np.empty((B, a.n_classes), dt)
     Upre = np.empty_like(U)
+    parg = np.zeros(Pq.shape, np.int32)
     loss = C.c_double()
     labels = np.ascontiguousarray(labels, np.int32)
     getattr(lib(), "nfo_aux_fwd_loss_" + _suf(dt))(
         C.byref(a), C.c_int32(B), _p(y), _p(labels), _p(Wa), _p(ba), _p(Wf), _p(bf),
-        _p(U), _p(Pq), _p(z), C.byref(loss), _p(dz), _p(Upre))
-    return AuxFwd(U, Pq, z, float(loss.value), dz, Upre)
+        _p(U), _p(Pq), _p(z), C.byref(loss), _p(dz), _p(Upre), _p(parg))
+    return AuxFwd(U, Pq, z, float(loss.value), dz, Upre, parg)
 
 
 def local_bwd(d: LayerDesc, a: AuxDesc, x, x_skip, lf: LayerFwd, af: AuxFwd, Wa, Wf, mask_u=None, mask_z=None):
     """Gradients of the local loss w.r.t. the layer's and the head's parameters only.
 
-    mask_u / mask_z (uint8, shapes of U / Z) optionally replace the ReLU decisions U>0 / Z>0."""
+    mask_u / mask_z (uint8, shapes of U / Z) optionally replace the ReLU decisions U>0 / Z>0;
+    the head's max-pooling selection is taken from ``af.parg``."""
+    parg = None if af.parg is None else np.ascontiguousarray(af.parg, np.int32)
     mask_u = None if mask_u is None else np.ascontiguousarray(mask_u, np.uint8)
     mask_z = None if mask_z is None else np.ascontiguousarray(mask_z, np.uint8)
     dt = x.dtype
@@ -178,7 +188,7 @@ def local_bwd(d: LayerDesc, a: AuxDesc, x, x_skip, lf: LayerFwd, af: AuxFwd, Wa,
         C.byref(d), C.byref(a), C.c_int32(B), _p(x), _p(x_skip), _p(lf.Z), _p(lf.Y), _p(lf.arg),
         _p(af.U), _p(af.Pq), _p(af.dz), _p(Wa), _p(Wf),
         _p(g["W"]), _p(g["b"]), _p(g["Wp"]), _p(g["Wa"]), _p(g["ba"]), _p(g["Wf"]), _p(g["bf"]),
-        _p(g["dY"]), _p(g["dZ"]), _p(mask_u), _p(mask_z))
+        _p(g["dY"]), _p(g["dZ"]), _p(mask_u), _p(mask_z), _p(parg))
     return g
 
 

@@ -117,11 +117,13 @@ inline void adaptive_window(int i, int L, int O, int &lo, int &hi) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Eq. 2: z = gamma_n F_n beta_n x_{n+1};  Eq. 3 with cross-entropy, mean over the batch.
+// Eq. 2: z = gamma_n F_n beta_n x_{n+1};  Eq. 3 with cross-entropy (or mean squared error
+// against the one-hot label), mean over the batch.  F_n is adaptive average or max pooling.
 // ---------------------------------------------------------------------------------------
 template <typename T>
 void aux_fwd_loss(const nfo_aux_desc &a, int B, const T *y, const int32_t *labels, const T *Wa,
-                  const T *ba, const T *Wf, const T *bf, T *U, T *Pq, T *z, double *loss, T *dz, T *Upre) {
+                  const T *ba, const T *Wf, const T *bf, T *U, T *Pq, T *z, double *loss, T *dz, T *Upre,
+                  int32_t *parg) {
   const int K = a.C_in, H = a.H_in, Wd = a.W_in, A = a.A, R = a.R, S = a.S, p = a.pad;
   const int oh = a.pool_oh, ow = a.pool_ow, Cls = a.n_classes, F = A * oh * ow;
   // beta_n: stride-1 convolution, output has the input's spatial size when 2*pad = R-1
@@ -144,7 +146,8 @@ void aux_fwd_loss(const nfo_aux_desc &a, int B, const T *y, const int32_t *label
           if (a.relu && acc < 0.0) acc = 0.0;
           U[((int64_t)(n * A + q) * Hu + i) * Wu + j] = (T)acc;
         }
-  // F_n: adaptive average pooling to oh x ow
+  // F_n: adaptive pooling to oh x ow -- the mean of each window, or its maximum (then parg
+  // records the flat position h*Wu+w of the first maximal element in row-major window order)
 #pragma omp parallel for collapse(2) schedule(static)
   for (int n = 0; n < B; ++n)
     for (int q = 0; q < A; ++q)
@@ -153,10 +156,23 @@ void aux_fwd_loss(const nfo_aux_desc &a, int B, const T *y, const int32_t *label
           int h0, h1, w0, w1;
           adaptive_window(i, Hu, oh, h0, h1);
           adaptive_window(j, Wu, ow, w0, w1);
+          const int64_t f = (int64_t)n * F + (q * oh + i) * ow + j;
+          if (a.head_pool == 1) {
+            T best = U[((int64_t)(n * A + q) * Hu + h0) * Wu + w0];
+            int bi = h0 * Wu + w0;
+            for (int h = h0; h < h1; ++h)
+              for (int w = w0; w < w1; ++w) {
+                const T u = U[((int64_t)(n * A + q) * Hu + h) * Wu + w];
+                if (u > best) best = u, bi = h * Wu + w;
+              }
+            Pq[f] = best;
+            if (parg) parg[f] = bi;
+            continue;
+          }
           double acc = 0.0;
           for (int h = h0; h < h1; ++h)
             for (int w = w0; w < w1; ++w) acc += (double)U[((int64_t)(n * A + q) * Hu + h) * Wu + w];
-          Pq[(int64_t)n * F + (q * oh + i) * ow + j] = (T)(acc / (double)((h1 - h0) * (w1 - w0)));
+          Pq[f] = (T)(acc / (double)((h1 - h0) * (w1 - w0)));
         }
   // gamma_n: linear layer
 #pragma omp parallel for collapse(2) schedule(static)
@@ -166,8 +182,19 @@ void aux_fwd_loss(const nfo_aux_desc &a, int B, const T *y, const int32_t *label
       for (int f = 0; f < F; ++f) acc += (double)Wf[(int64_t)c * F + f] * (double)Pq[(int64_t)n * F + f];
       z[(int64_t)n * Cls + c] = (T)acc;
     }
-  // softmax cross-entropy, mean over the batch, and its derivative w.r.t. the logits
   double total = 0.0;
+  if (a.loss_kind == 1) {
+    // mean squared error against the one-hot label: mean over the classes, then over the batch
+    for (int n = 0; n < B; ++n)
+      for (int c = 0; c < Cls; ++c) {
+        const double e = (double)z[(int64_t)n * Cls + c] - (c == labels[n] ? 1.0 : 0.0);
+        total += e * e;
+        dz[(int64_t)n * Cls + c] = (T)(2.0 * e / ((double)B * (double)Cls));
+      }
+    *loss = total / ((double)B * (double)Cls);
+    return;
+  }
+  // softmax cross-entropy, mean over the batch, and its derivative w.r.t. the logits
   for (int n = 0; n < B; ++n) {
     const T *zn = z + (int64_t)n * Cls;
     double m = (double)zn[0];
@@ -191,7 +218,7 @@ template <typename T>
 void local_bwd(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *x, const T *xs,
                const T *Z, const T *Y, const int32_t *arg, const T *U, const T *Pq, const T *dz,
                const T *Wa, const T *Wf, T *dW, T *db, T *dWp, T *dWa, T *dba, T *dWf, T *dbf,
-               T *dY_out, T *dZ_out, const uint8_t *mask_u, const uint8_t *mask_z) {
+               T *dY_out, T *dZ_out, const uint8_t *mask_u, const uint8_t *mask_z, const int32_t *parg) {
   // mask_u / mask_z (optional): the two ReLU decisions "U > 0" and "Z > 0" handed in by the
   // caller instead of being taken here.  They exist for comparisons against an implementation
   // that accumulates in another precision: where a pre-activation is zero to within rounding,
@@ -239,7 +266,12 @@ void local_bwd(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *x
               adaptive_window(i, Hu, oh, h0, h1);
               adaptive_window(j, Wu, ow, w0, w1);
               if (h < h0 || h >= h1 || w < w0 || w >= w1) continue;
-              acc += (double)dPq[(size_t)n * F + (q * oh + i) * ow + j] / (double)((h1 - h0) * (w1 - w0));
+              const size_t f = (size_t)n * F + (q * oh + i) * ow + j;
+              if (a.head_pool == 1) {  // max pooling hands the gradient to the selected element
+                if (parg[f] == h * Wu + w) acc += (double)dPq[f];
+                continue;
+              }
+              acc += (double)dPq[f] / (double)((h1 - h0) * (w1 - w0));
             }
           const int64_t e = ((int64_t)(n * A + q) * Hu + h) * Wu + w;
           const bool on = mask_u ? mask_u[e] != 0 : U[e] > (T)0;
@@ -398,15 +430,16 @@ void local_step(const nfo_layer_desc &d, const nfo_aux_desc &a, int B, const T *
                 nWa = (int64_t)A * K * a.R * a.S, nWf = (int64_t)Cls * F;
   std::vector<T> Z((size_t)B * K * o.Ho * o.Wo), U((size_t)B * A * Hu * Wu), Pq((size_t)B * F),
       z((size_t)B * Cls), dz((size_t)B * Cls);
-  std::vector<int32_t> arg(d.pool_kind ? (size_t)B * K * o.Hp * o.Wp : 0);
+  std::vector<int32_t> arg(d.pool_kind ? (size_t)B * K * o.Hp * o.Wp : 0), parg((size_t)B * F);
   std::vector<T> tW(nW), tb(K), tWp(nWp), tWa(nWa), tba(A), tWf(nWf), tbf(Cls);
   // lines 3-5 of Algorithm 2
   layer_fwd<T>(d, B, x, xs, W, b, Wp, Z.data(), Y, arg.empty() ? nullptr : arg.data());
-  aux_fwd_loss<T>(a, B, Y, labels, Wa, ba, Wf, bf, U.data(), Pq.data(), z.data(), loss, dz.data(), nullptr);
+  aux_fwd_loss<T>(a, B, Y, labels, Wa, ba, Wf, bf, U.data(), Pq.data(), z.data(), loss, dz.data(), nullptr,
+                  parg.data());
   // line 6
   local_bwd<T>(d, a, B, x, xs, Z.data(), Y, arg.empty() ? nullptr : arg.data(), U.data(), Pq.data(),
                dz.data(), Wa, Wf, tW.data(), tb.data(), nWp ? tWp.data() : nullptr, tWa.data(), tba.data(),
-               tWf.data(), tbf.data(), nullptr, nullptr, nullptr, nullptr);
+               tWf.data(), tbf.data(), nullptr, nullptr, nullptr, nullptr, parg.data());
   // line 7
   sgd_update<T>(nW, W, tW.data(), vW, lr, mu);
   sgd_update<T>(K, b, tb.data(), vb, lr, mu);
@@ -458,16 +491,16 @@ void nfo_set_num_threads(int32_t n) {
   }                                                                                                \
   void nfo_aux_fwd_loss_##SUF(const nfo_aux_desc *a, int32_t B, const T *y, const int32_t *labels, \
                               const T *Wa, const T *ba, const T *Wf, const T *bf, T *U, T *Pq,     \
-                              T *z, double *loss, T *dz, T *Upre) {                                \
-    aux_fwd_loss<T>(*a, B, y, labels, Wa, ba, Wf, bf, U, Pq, z, loss, dz, Upre);                   \
+                              T *z, double *loss, T *dz, T *Upre, int32_t *parg) {                 \
+    aux_fwd_loss<T>(*a, B, y, labels, Wa, ba, Wf, bf, U, Pq, z, loss, dz, Upre, parg);             \
   }                                                                                                \
   void nfo_local_bwd_##SUF(const nfo_layer_desc *d, const nfo_aux_desc *a, int32_t B, const T *x,  \
                            const T *x_skip, const T *Z, const T *Y, const int32_t *arg,            \
                            const T *U, const T *Pq, const T *dz, const T *Wa, const T *Wf, T *dW,  \
                            T *db, T *dWp, T *dWa, T *dba, T *dWf, T *dbf, T *dY, T *dZ,            \
-                           const uint8_t *mask_u, const uint8_t *mask_z) {                         \
+                           const uint8_t *mask_u, const uint8_t *mask_z, const int32_t *parg) {    \
     local_bwd<T>(*d, *a, B, x, x_skip, Z, Y, arg, U, Pq, dz, Wa, Wf, dW, db, dWp, dWa, dba, dWf,   \
-                 dbf, dY, dZ, mask_u, mask_z);                                                     \
+                 dbf, dY, dZ, mask_u, mask_z, parg);                                               \
   }                                                                                                \
   void nfo_sgd_update_##SUF(int64_t numel, T *w, const T *g, T *v, double lr, double mu) {         \
     sgd_update<T>(numel, w, g, v, lr, mu);                                                         \

@@ -28,10 +28,11 @@ def _spec(C=2, H=5, W=5, K=3, A=2, R=3, S=3, stride=1, pad=1, pool=None, skip=0)
     return ls
 
 
-def _setup(o, ls, B=2, Cls=3, seed=7, dtype=np.float64, relu=1):
+def _setup(o, ls, B=2, Cls=3, seed=7, dtype=np.float64, relu=1, head_pool=0, loss_kind=0):
     d = o.layer_desc(**ls.layer_desc_fields())
     af = ls.aux_desc_fields(Cls)
     af["relu"] = relu
+    af["head_pool"], af["loss_kind"] = head_pool, loss_kind
     a = o.aux_desc(**af)
     g = workloads.rng_for(seed, "pin", ls.C_in, ls.H_in, ls.C_out, ls.stride, ls.pool_kind, ls.skip_kind)
     x = g.standard_normal((B, ls.C_in, ls.H_in, ls.W_in)).astype(dtype)
@@ -564,3 +565,106 @@ def test_block_epoch_is_the_sequence_of_local_steps(oracle):
     y1 = o.layer_fwd(d1, y0, None, p1["W"], p1["b"]).Y
     want = o.aux_fwd_loss(a1, y1, lab, p1["Wa"], p1["ba"], p1["Wf"], p1["bf"]).loss
     assert abs(la[0, 1] - want) < 1e-12
+
+
+# ---- head variants the paper names: max pooling as F_n, mean squared error as the loss --------
+VARIANTS = {"max_ce": (1, 0), "avg_mse": (0, 1), "max_mse": (1, 1)}
+VARIANT_SHAPES = ["plain5x5", "hp4", "hp3_odd_overlap", "hp2", "hp1", "rect", "pool2", "skip_proj"]
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("name", VARIANT_SHAPES)
+def test_variant_finite_difference_gradients(oracle, name, variant):
+    o = oracle
+    hp, lk = VARIANTS[variant]
+    ls = _spec(**SHAPES[name])
+    d, a, x, xs, labels, p = _setup(o, ls, head_pool=hp, loss_kind=lk)
+    _, _, g = _grads(o, d, a, x, xs, labels, p)
+    h = 1e-6
+    for key in o.PARAM_NAMES:
+        if p[key] is None:
+            continue
+        flat = p[key].reshape(-1)
+        num = np.zeros_like(flat)
+        for e in range(flat.size):
+            keep = flat[e]
+            flat[e] = keep + h
+            lp = _loss(o, d, a, x, xs, labels, p)
+            flat[e] = keep - h
+            lm = _loss(o, d, a, x, xs, labels, p)
+            flat[e] = keep
+            num[e] = (lp - lm) / (2 * h)
+        ana = g[key].reshape(-1)
+        scale = max(np.abs(num).max(), 1e-3)
+        assert np.abs(num - ana).max() <= 2e-6 * scale + 1e-8, (name, variant, key, np.abs(num - ana).max(), scale)
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("name", VARIANT_SHAPES)
+def test_variant_matches_torch_autograd(oracle, name, variant):
+    o = oracle
+    hp, lk = VARIANTS[variant]
+    ls = _spec(**SHAPES[name])
+    d, a, x, xs, labels, p = _setup(o, ls, B=3, Cls=4, seed=11, head_pool=hp, loss_kind=lk)
+    lr, mu = 0.05, 0.9
+    ta = SimpleNamespace(**ls.aux_desc_fields(4), head_pool=hp, loss_kind=lk)
+    ref, final = torch_ref.local_step(SimpleNamespace(**ls.layer_desc_fields()), ta, x, xs, labels, p, lr, mu, steps=3)
+    mom = {k: (None if v is None else np.zeros_like(v)) for k, v in p.items()}
+    for step in range(3):
+        Y, loss, g = o.local_step(d, a, x, xs, labels, p, mom, lr, mu)
+        rl, rg, ry = ref[step]
+        assert abs(loss - rl) <= 1e-12 * max(1, abs(rl))
+        for k in rg:
+            np.testing.assert_allclose(g[k], rg[k], rtol=1e-9, atol=1e-12, err_msg=f"{name}:{variant}:{k}:{step}")
+    for k in final:
+        np.testing.assert_allclose(p[k], final[k], rtol=1e-10, atol=1e-12, err_msg=f"{name}:{variant}:{k}")
+
+
+def test_variant_closed_forms(oracle):
+    o = oracle
+    g = workloads.rng_for(6, "variants")
+    B, Cls = 5, 4
+    y = np.abs(g.standard_normal((B, 3, 6, 6)))
+    Wa, ba = g.standard_normal((2, 3, 3, 3)), g.standard_normal((2,))
+    labels = g.integers(0, Cls, size=(B,)).astype(np.int32)
+    # MSE at zero linear weights: every logit is 0, the one-hot target has one 1 -> loss = 1/Cls,
+    # dL/dz = 2 (0 - t) / (B Cls)
+    a = o.aux_desc(3, 6, 6, 2, Cls, loss_kind=1)
+    af = o.aux_fwd_loss(a, y, labels, Wa, ba, np.zeros((Cls, 8)), np.zeros((Cls,)))
+    assert abs(af.loss - 1.0 / Cls) < 1e-15
+    t = np.eye(Cls)[labels]
+    np.testing.assert_allclose(af.dz, -2.0 * t / (B * Cls), rtol=1e-14)
+    # MSE with logits forced to the target by the bias of a one-class-per-sample batch is 0
+    Wf, bf = g.standard_normal((Cls, 8)), g.standard_normal((Cls,))
+    af = o.aux_fwd_loss(a, y, labels, Wa, ba, Wf, bf)
+    want = np.mean((af.Pq @ Wf.T + bf - t) ** 2)
+    assert abs(af.loss - want) < 1e-13
+    # max pooling: windows of a 6x6 map are its 3x3 quadrants; parg points at the maximum; 2x2 map:
+    # max == avg == identity
+    am = o.aux_desc(3, 6, 6, 2, Cls, head_pool=1)
+    afm = o.aux_fwd_loss(am, y, labels, Wa, ba, Wf, bf)
+    want = afm.U.reshape(B, 2, 2, 3, 2, 3).max(axis=(3, 5)).reshape(B, 8)
+    assert np.array_equal(afm.Pq, want)
+    flatU = afm.U.reshape(B, 2, 36)
+    pa = afm.parg.reshape(B, 2, 4)
+    assert np.array_equal(np.take_along_axis(flatU, pa.astype(np.int64), axis=2).reshape(B, 8), afm.Pq)
+    hh, ww = pa // 6, pa % 6
+    cells = np.arange(4).reshape(1, 1, 4)
+    assert np.all(hh // 3 == cells // 2) and np.all(ww // 3 == cells % 2)
+    y2 = np.abs(g.standard_normal((B, 3, 2, 2)))
+    a2m, a2a = o.aux_desc(3, 2, 2, 2, Cls, head_pool=1), o.aux_desc(3, 2, 2, 2, Cls)
+    assert np.array_equal(o.aux_fwd_loss(a2m, y2, labels, Wa, ba, Wf, bf).Pq,
+                          o.aux_fwd_loss(a2a, y2, labels, Wa, ba, Wf, bf).Pq)
+    # an all-zero window (everything cut by the head's ReLU): first element selected, no gradient
+    y0 = np.zeros((1, 3, 4, 4))
+    a0 = o.aux_desc(3, 4, 4, 2, Cls, head_pool=1)
+    af0 = o.aux_fwd_loss(a0, y0, labels[:1], Wa, -np.abs(ba), Wf, bf)
+    assert np.array_equal(af0.parg.reshape(2, 2, 2), np.broadcast_to(np.array([[0, 2], [8, 10]]), (2, 2, 2)))
+    ls = workloads.LayerSpec("t", 3, 4, 4, 3, A=2)
+    d0 = o.layer_desc(**ls.layer_desc_fields())
+    x0 = g.standard_normal((1, 3, 4, 4))
+    W0, b0 = g.standard_normal((3, 3, 3, 3)), g.standard_normal((3,))
+    lf = o.layer_fwd(d0, x0, None, W0, b0)
+    af0 = o.aux_fwd_loss(a0, lf.Y, labels[:1], Wa * 0, -np.abs(ba) - 1, Wf, bf)
+    gr = o.local_bwd(d0, a0, x0, None, lf, af0, Wa * 0, Wf)
+    assert not gr["Wa"].any() and not gr["W"].any() and gr["Wf"].shape == (Cls, 8)

@@ -21,9 +21,13 @@ def local_loss(d, a, x, x_skip, labels, p):
     u = F.conv2d(y, p["Wa"], p["ba"], stride=1, padding=a.pad)
     if a.relu:
         u = torch.relu(u)
-    q = F.adaptive_avg_pool2d(u, (a.pool_oh, a.pool_ow)).flatten(1)
+    pool = F.adaptive_max_pool2d if getattr(a, "head_pool", 0) == 1 else F.adaptive_avg_pool2d
+    q = pool(u, (a.pool_oh, a.pool_ow)).flatten(1)
     logits = F.linear(q, p["Wf"], p["bf"])
-    loss = F.cross_entropy(logits, labels.long(), reduction="mean")
+    if getattr(a, "loss_kind", 0) == 1:
+        loss = F.mse_loss(logits, F.one_hot(labels.long(), logits.shape[1]).to(logits.dtype), reduction="mean")
+    else:
+        loss = F.cross_entropy(logits, labels.long(), reduction="mean")
     return loss, y
 
 
