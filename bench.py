@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prof", action="store_true")
     ap.add_argument("--lr", type=float, default=None, help="override the configuration's learning rate")
+    ap.add_argument("--head-pool", choices=["avg", "max"], default="avg", help="the heads' down-sampling F_n")
+    ap.add_argument("--loss", choices=["ce", "mse"], default="ce", help="the local loss of Eq. 3")
     ap.add_argument("--trace-loss", action="store_true", help="print every layer's loss after each step (syncs)")
     ap.add_argument("--traffic-calib", action="store_true",
                     help="only run 5 plain copies of 1 GiB (nf_cache_read, contiguous rows): the known-size kernel "
@@ -105,6 +107,7 @@ def main():
     for li, ls in enumerate(cfg.layers):
         p = workloads.gen_layer_params(cfg.seed, li, ls, cls)
         d, a = nf.LayerDesc(**ls.layer_desc_fields()), nf.AuxDesc(**ls.aux_desc_fields(cls))
+        a.head_pool, a.loss_kind = int(args.head_pool == "max"), int(args.loss == "mse")
         B = cfg.blocks[ls.block].batch
         L = LocalLayer(d, a, layout.params_to_lib(p, ls.A), B, momentum=cfg.momentum != 0, device=dev)
         L.y = L.new_output(B)
@@ -366,7 +369,8 @@ def main():
         "config": {"workload": f"{cfg.name}: one local step of each of {len(cfg.layers)} layers at block batches "
                                f"{'/'.join(str(b.batch) for b in cfg.blocks)}, {cls} classes, SGD lr {cfg.lr} "
                                f"momentum {cfg.momentum}, cache read (shuffled gather) before and cache write after "
-                               f"every block", "images_per_step": images_per_step, "samples": N,
+                               f"every block" + ("" if (args.head_pool, args.loss) == ("avg", "ce") else
+                                                 f"; heads: {args.head_pool} pooling, {args.loss} loss"), "images_per_step": images_per_step, "samples": N,
                    "gflop_per_step": round(flops_per_step / 1e9, 1)},
         "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
         "losses_finite": finite,

@@ -68,13 +68,19 @@ typedef struct {
 } nf_layer_desc;
 
 /* Auxiliary head A_n of Eq. 2: conv beta_n (R x S, stride 1, pad, + bias, ReLU if relu),
- * adaptive average pool F_n to pool_oh x pool_ow, linear gamma_n to n_classes.
- * C_in/H_in/W_in describe the tensor the layer emits (post-pool). */
+ * adaptive pooling F_n to pool_oh x pool_ow (average or max: the two down-sampling mechanisms
+ * the text below Eq. 1 names), linear gamma_n to n_classes.  The loss l of Eq. 3 is softmax
+ * cross-entropy, or the mean squared error against the one-hot label (mean over the classes,
+ * then over the batch).  C_in/H_in/W_in describe the tensor the layer emits (post-pool). */
+enum { NF_HEAD_POOL_AVG = 0, NF_HEAD_POOL_MAX = 1 };
+enum { NF_LOSS_CE = 0, NF_LOSS_MSE = 1 };
 typedef struct {
   int32_t C_in, H_in, W_in;
   int32_t A, R, S, pad, relu;
   int32_t pool_oh, pool_ow;
   int32_t n_classes;
+  int32_t head_pool; /* NF_HEAD_POOL_*; ties of the max go to the first element in row-major order */
+  int32_t loss_kind; /* NF_LOSS_* */
 } nf_aux_desc;
 
 typedef struct {
@@ -105,8 +111,10 @@ int32_t nf_workspace_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t
  *   NF_WS_AUX_ACT   the head's convolution output after its ReLU (Eq. 2, beta_n), fp32
  *                   [B][Hu][Wu][A];
  *   NF_WS_POOL_ARG  one byte per emitted element [B][Hp][Wp][C_out]: index u*pool_k+v of the
- *                   window cell the max-pool P_n of Eq. 1 selected (size 0 when un-pooled). */
-enum { NF_WS_AUX_ACT = 0, NF_WS_POOL_ARG = 1 };
+ *                   window cell the max-pool P_n of Eq. 1 selected (size 0 when un-pooled);
+ *   NF_WS_HEAD_ARG  int32 [B][pool_oh][pool_ow][A]: flat position h*Wu+w inside the head's
+ *                   convolution output that a max-pooling F_n selected (size 0 when F_n averages). */
+enum { NF_WS_AUX_ACT = 0, NF_WS_POOL_ARG = 1, NF_WS_HEAD_ARG = 2 };
 int32_t nf_workspace_region(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, int32_t which,
                             size_t *offset, size_t *bytes);
 

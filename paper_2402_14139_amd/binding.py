@@ -22,7 +22,9 @@ EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_f
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
            "nf_block_train_epoch", "nf_block_fill_cache")
 
-NF_WS_AUX_ACT, NF_WS_POOL_ARG = 0, 1
+NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
+NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
+NF_LOSS_CE, NF_LOSS_MSE = 0, 1
 
 
 class NfError(RuntimeError):
@@ -40,7 +42,8 @@ class LayerDesc(C.Structure):
 
 class AuxDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
-        "C_in", "H_in", "W_in", "A", "R", "S", "pad", "relu", "pool_oh", "pool_ow", "n_classes")]
+        "C_in", "H_in", "W_in", "A", "R", "S", "pad", "relu", "pool_oh", "pool_ow", "n_classes",
+        "head_pool", "loss_kind")]
 
 
 class SgdDesc(C.Structure):

@@ -1,6 +1,7 @@
 // The auxiliary head after its convolution (NeuroFlux, arXiv 2402.14139, Eq. 2 and Eq. 3):
-// adaptive average pooling F_n, the linear layer gamma_n, softmax cross-entropy with the
-// batch mean, and the backward of those three (gradient line of Algorithm 2).
+// adaptive average (or max) pooling F_n, the linear layer gamma_n, softmax cross-entropy (or
+// mean squared error against the one-hot label) with the batch mean, and the backward of those
+// three (gradient line of Algorithm 2).
 // These steps are tiny next to the convolutions; they are written as fused wavefront /
 // workgroup reductions with a fixed summation order (deterministic).
 #include "nf_internal.h"
@@ -26,17 +27,20 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
-// F_n: adaptive average pool.  A workgroup serves G (sample, output cell) pairs; each pair has
-// CA channel lanes (V channels each, 16-byte accesses when V == 4) x NS window-position slices,
-// CA * NS * G = HT.  Slice sums are added in order through LDS.
+// F_n: adaptive average pool (PMAX: adaptive max pool, which also records the flat position
+// h*Wu+w of the first maximal element in row-major window order).  A workgroup serves G (sample,
+// output cell) pairs; each pair has CA channel lanes (V channels each, 16-byte accesses when
+// V == 4) x NS window-position slices, CA * NS * G = HT.  Slice results are combined in order
+// through LDS.
 // With splits > 0 the aux activation does not exist yet: it is formed here from the raw partial
 // sums of the split aux convolution, U = act(sum_z part[z] + ba), and written out on the way.
-template <int V>
+template <int V, bool PMAX>
 __global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__restrict__ U,
                                                        const float *__restrict__ part, int splits,
                                                        const float *__restrict__ ba, float *__restrict__ Pq,
-                                                       int CA, int NS) {
+                                                       int32_t *__restrict__ parg, int CA, int NS) {
   __shared__ float red[HT * V];
+  __shared__ int redi[PMAX ? HT * V : 1];
   const int t = threadIdx.x;
   const int per = CA * NS, G = HT / per;
   const int grp = t / per, tg = t - grp * per;
@@ -56,8 +60,9 @@ __global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__res
   for (int c0 = 0; c0 < AV; c0 += CA) {
     const int col = c0 + lane;
     float acc[V];
+    int bpos[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    for (int e = 0; e < V; ++e) acc[e] = PMAX ? -INFINITY : 0.f, bpos[e] = 0x7fffffff;
     if (live && col < AV) {
       float bias[V];
 #pragma unroll
@@ -98,19 +103,42 @@ __global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__res
           }
         }
 #pragma unroll
-        for (int e = 0; e < V; ++e) acc[e] += v[e];
+        for (int e = 0; e < V; ++e) {
+          if constexpr (PMAX) {
+            if (v[e] > acc[e]) acc[e] = v[e], bpos[e] = hh * s.Wu + wx;  // strict: first maximum of the slice
+          } else {
+            acc[e] += v[e];
+          }
+        }
       }
     }
     __syncthreads();  // previous round's reads of red are done
 #pragma unroll
-    for (int e = 0; e < V; ++e) red[t * V + e] = acc[e];
+    for (int e = 0; e < V; ++e) {
+      red[t * V + e] = acc[e];
+      if constexpr (PMAX) redi[t * V + e] = bpos[e];
+    }
     __syncthreads();
     if (live && slice == 0 && col < AV) {
 #pragma unroll
       for (int e = 0; e < V; ++e) {
-        float sum = acc[e];
-        for (int k = 1; k < NS; ++k) sum += red[(grp * per + k * CA + lane) * V + e];
-        Pq[(long long)n * s.F + cell * s.A + col * V + e] = sum * inv;
+        const long long o = (long long)n * s.F + cell * s.A + col * V + e;
+        if constexpr (PMAX) {
+          float best = acc[e];
+          int bp = bpos[e];
+          for (int k = 1; k < NS; ++k) {
+            const int at = (grp * per + k * CA + lane) * V + e;
+            const float cv = red[at];
+            const int cp = redi[at];
+            if (cv > best || (cv == best && cp < bp)) best = cv, bp = cp;  // ties: earliest position
+          }
+          Pq[o] = best;
+          parg[o] = bp;
+        } else {
+          float sum = acc[e];
+          for (int k = 1; k < NS; ++k) sum += red[(grp * per + k * CA + lane) * V + e];
+          Pq[o] = sum * inv;
+        }
       }
     }
   }
@@ -148,6 +176,30 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
   __syncthreads();
 
   const int lane = t & 63, wave = t >> 6;
+  if (s.mse) {
+    // squared error against the one-hot label, mean over the classes (the batch mean follows)
+    const int y = labels[n];
+    const float sc = 2.f / ((float)s.B * (float)s.Cls);
+    float se = 0.f;
+    for (int q = t; q < s.Cls; q += HT) {
+      const float e = z[q] - (q == y ? 1.f : 0.f);
+      se += e * e;
+      dz[(long long)n * s.Cls + q] = e * sc;
+    }
+    se = wave_sum(se);
+    if (lane == 0) red[wave] = se;
+    __syncthreads();
+    if (t == 0) loss_n[n] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)s.Cls;
+    for (int q = t; q < s.Cls; q += HT) z[q] = (z[q] - (q == y ? 1.f : 0.f)) * sc;
+    __syncthreads();
+    for (int f = t; f < s.F; f += HT) {
+      float acc = 0.f;
+#pragma unroll 4
+      for (int q = 0; q < s.Cls; ++q) acc += z[q] * Wf[(long long)q * s.F + f];
+      dPq[(long long)n * s.F + f] = acc;
+    }
+    return;
+  }
   float m = -INFINITY;
   for (int q = t; q < s.Cls; q += HT) m = fmaxf(m, z[q]);
   m = wave_max(m);
@@ -229,7 +281,21 @@ __global__ __launch_bounds__(WT) void head_fc_wide_kernel(HeadShape s, const flo
   }
   __syncthreads();
   const float invB = 1.f / (float)s.B;
-  if (wave < ng) {
+  if (wave < ng && s.mse) {
+    const int g = wave;
+    float *zg = z + g * s.Cls;
+    const int y = labels[n0 + g];
+    const float sc = 2.f / ((float)s.B * (float)s.Cls);
+    float se = 0.f;
+    for (int q = lane; q < s.Cls; q += 64) {
+      const float e = zg[q] - (q == y ? 1.f : 0.f);
+      se += e * e;
+      dz[(long long)(n0 + g) * s.Cls + q] = e * sc;
+      zg[q] = e * sc;
+    }
+    se = wave_sum(se);
+    if (lane == 0) loss_n[n0 + g] = se / (float)s.Cls;
+  } else if (wave < ng) {
     const int g = wave;
     float *zg = z + g * s.Cls;
     float m = -INFINITY;
@@ -290,7 +356,8 @@ __global__ __launch_bounds__(HT) void loss_mean_kernel(const float *__restrict__
 //               feature lanes x (256/fch) batch slices, slice sums added in order through LDS.
 //               dWf[q][f] = sum_n dz[n][q] * Pq[n][f]; chunk 0 also forms dbf[q] = sum_n dz[n][q].
 //   then nb_u   F_n backward + aux ReLU mask: dU = [U > 0] * sum over windows containing (h,w)
-//               of dPq / |window|, V channels per thread;
+//               of dPq / |window| (max pooling: of dPq where the window selected (h,w)), V
+//               channels per thread;
 //   then nb_t   re-lay of the aux filter for the data gradient: WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k];
 //   then 0/1    batch mean of the per-sample losses (when loss_out is given).
 struct HeadBwdJobs {
@@ -303,7 +370,8 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
                                                       const float *__restrict__ dPq, float *__restrict__ dU,
                                                       const float *__restrict__ Wa, float *__restrict__ WaT, int R,
                                                       int S, int K, const float *__restrict__ loss_n,
-                                                      float *__restrict__ loss_out) {
+                                                      float *__restrict__ loss_out,
+                                                      const int32_t *__restrict__ parg) {
   __shared__ float red[HT];
   __shared__ float redb[HT];
   int b = blockIdx.x;
@@ -365,10 +433,17 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
         int w0, w1;
         adaptive_window(cj, s.Wu, s.ow, w0, w1);
         if (w < w0 || w >= w1) continue;
-        const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
-        const float *src = dPq + (long long)n * s.F + (ci * s.ow + cj) * s.A + av * V;
+        const long long fo = (long long)n * s.F + (ci * s.ow + cj) * s.A + av * V;
+        const float *src = dPq + fo;
+        if (s.pmax) {  // max pooling hands the gradient to the element it selected
 #pragma unroll
-        for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
+          for (int e = 0; e < V; ++e)
+            if (parg[fo + e] == hh * s.Wu + w) acc[e] += src[e];
+        } else {
+          const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
+#pragma unroll
+          for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
+        }
       }
     }
 #pragma unroll
@@ -401,7 +476,7 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
 }  // namespace
 
 hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
-                            hipStream_t st) {
+                            int32_t *parg, hipStream_t st) {
   const int V = h.A % 4 == 0 ? 4 : 1;
   const int AV = h.A / V;
   int CA = 1;
@@ -413,10 +488,16 @@ hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int
   const int G = HT / (CA * NS);
   const long long pairs = (long long)h.B * h.oh * h.ow;
   const dim3 grid((unsigned)((pairs + G - 1) / G));
-  if (V == 4)
-    hipLaunchKernelGGL(head_pool_kernel<4>, grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, CA, NS);
-  else
-    hipLaunchKernelGGL(head_pool_kernel<1>, grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, CA, NS);
+  if (h.pmax) {
+    if (V == 4)
+      hipLaunchKernelGGL((head_pool_kernel<4, true>), grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, parg, CA, NS);
+    else
+      hipLaunchKernelGGL((head_pool_kernel<1, true>), grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, parg, CA, NS);
+  } else if (V == 4) {
+    hipLaunchKernelGGL((head_pool_kernel<4, false>), grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, parg, CA, NS);
+  } else {
+    hipLaunchKernelGGL((head_pool_kernel<1, false>), grid, dim3(HT), 0, st, h, U, part, splits, ba, Pq, parg, CA, NS);
+  }
   return hipGetLastError();
 }
 
@@ -441,7 +522,7 @@ hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStre
 
 hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,
                            const float *U, const float *dPq, float *dU, const float *Wa, float *WaT, int R, int S,
-                           int K, const float *loss_n, float *loss_out, hipStream_t st) {
+                           int K, const float *loss_n, float *loss_out, const int32_t *parg, hipStream_t st) {
   HeadBwdJobs jb;
   // feature lanes per workgroup: few, so that many batch slices share the reduction over n
   jb.fch = 8;
@@ -455,10 +536,10 @@ hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz,
   const dim3 grid((unsigned)(jb.nb_w + jb.nb_u + jb.nb_t + (loss_out ? 1 : 0)));
   if (V == 4)
     hipLaunchKernelGGL(head_bwd_kernel<4>, grid, dim3(HT), 0, st, h, jb, Pq, dz, dWf, dbf, U, dPq, dU, Wa, WaT, R, S, K,
-                       loss_n, loss_out);
+                       loss_n, loss_out, parg);
   else
     hipLaunchKernelGGL(head_bwd_kernel<1>, grid, dim3(HT), 0, st, h, jb, Pq, dz, dWf, dbf, U, dPq, dU, Wa, WaT, R, S, K,
-                       loss_n, loss_out);
+                       loss_n, loss_out, parg);
   return hipGetLastError();
 }
 

@@ -63,6 +63,7 @@ int32_t check_aux(const nf_aux_desc *a, AuxDims *o) {
       a->pool_oh <= 0 || a->pool_ow <= 0 || a->n_classes <= 0)
     return NF_ERR_BAD_DESC;
   if (a->R != a->S || a->R > 15 || a->pad > a->R - 1) return NF_ERR_UNSUPPORTED;
+  if (a->head_pool < 0 || a->head_pool > 1 || a->loss_kind < 0 || a->loss_kind > 1) return NF_ERR_UNSUPPORTED;
   o->Hu = a->H_in + 2 * a->pad - a->R + 1;
   o->Wu = a->W_in + 2 * a->pad - a->S + 1;
   if (o->Hu <= 0 || o->Wu <= 0) return NF_ERR_BAD_DESC;
@@ -96,7 +97,7 @@ WgradProblem aux_wgrad_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
 }
 
 struct WsLayout {
-  size_t T_dZ, arg, U, Pq, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
+  size_t T_dZ, arg, U, Pq, parg, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
   // reduction splits of the forward-type contractions (1 = none); their partial sums alias `part`
   int ksplits_aux, ksplits_layer, ksplits_dgrad;
@@ -125,6 +126,7 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     const size_t u = (size_t)B * ad.Hu * ad.Wu * a->A;
     w.U = take(u * f);
     w.Pq = take((size_t)B * ad.F * f);
+    w.parg = take(a->head_pool == 1 ? (size_t)B * ad.F * sizeof(int32_t) : 0);
     w.dz = take((size_t)B * a->n_classes * f);
     w.loss_n = take((size_t)B * f);
     w.dPq = take((size_t)B * ad.F * f);
@@ -286,7 +288,7 @@ int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const 
 HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
   HeadShape h;
   h.B = B, h.Hu = ad.Hu, h.Wu = ad.Wu, h.A = a->A, h.oh = a->pool_oh, h.ow = a->pool_ow, h.F = ad.F,
-  h.Cls = a->n_classes, h.relu = a->relu;
+  h.Cls = a->n_classes, h.relu = a->relu, h.pmax = a->head_pool == 1, h.mse = a->loss_kind == 1;
   return h;
 }
 
@@ -310,7 +312,8 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   const HeadShape hs = head_shape(a, ad, B);
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
   NF_RUN(st, "head_pool", 0.0, 4.0 * (u * (ks ? ks + 1.0 : 1.0) + (double)B * ad.F),
-         launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.part), ks, ap->ba, wsf(ws, w.Pq), st));
+         launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.part), ks, ap->ba, wsf(ws, w.Pq),
+                          reinterpret_cast<int32_t *>(wsf(ws, w.parg)), st));
   NF_RUN(st, "head_fc", 4.0 * B * fc, 4.0 * (2.0 * B * fc + (double)B * (2.0 * ad.F + a->n_classes)),
          launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), wsf(ws, w.dPq), st));
   if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
@@ -334,7 +337,8 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
   const double wa = (double)a->A * a->R * a->S * a->C_in;
   NF_RUN(st, "head_bwd", 2.0 * B * fc, 4.0 * (fc + (double)B * (2.0 * ad.F + a->n_classes) + 2.0 * u) + 8.0 * wa,
          launch_head_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ga->Wf, ga->bf, wsf(ws, w.U), wsf(ws, w.dPq), dU, ap->Wa,
-                         wsf(ws, w.WaT), a->R, a->S, a->C_in, wsf(ws, w.loss_n), loss_out, st));
+                         wsf(ws, w.WaT), a->R, a->S, a->C_in, wsf(ws, w.loss_n), loss_out,
+                         reinterpret_cast<const int32_t *>(wsf(ws, w.parg)), st));
   // beta_n: weight + bias gradient
   {
     WgradProblem g = aux_wgrad_shape(a, ad, B);
@@ -508,6 +512,10 @@ int32_t nf_workspace_region(const nf_layer_desc *d, const nf_aux_desc *a, int32_
   } else if (which == NF_WS_POOL_ARG) {
     *offset = w.arg;
     *bytes = d->pool_kind ? (size_t)B * ld.Hp * ld.Wp * d->C_out : 0;
+  } else if (which == NF_WS_HEAD_ARG) {
+    if (!a) return NF_ERR_NULL;
+    *offset = w.parg;
+    *bytes = a->head_pool == 1 ? (size_t)B * ad.F * sizeof(int32_t) : 0;
   } else {
     return NF_ERR_BAD_DESC;
   }

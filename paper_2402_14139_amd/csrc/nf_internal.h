@@ -102,11 +102,14 @@ hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r, hipStream_t st);
 // ---- head (Eq. 2 after the aux conv, Eq. 3) ----
 struct HeadShape {
   int B, Hu, Wu, A, oh, ow, F, Cls, relu;
+  int pmax;  // F_n: 0 adaptive average pool, 1 adaptive max pool
+  int mse;   // loss: 0 softmax cross-entropy, 1 mean squared error against the one-hot label
 };
 // Pq = adaptive average pool of U.  With splits > 0, U is first formed from the raw partial sums
 // part[splits][B*Hu*Wu*A] of the aux convolution: U = act(sum_z part[z] + ba) (written out).
+// parg [B][F] (max pooling only): flat position h*Wu+w each pooled feature was taken from.
 hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
-                            hipStream_t st);
+                            int32_t *parg, hipStream_t st);
 // logits, softmax cross-entropy, dz, per-sample losses and dPq = dz * Wf
 hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
                           const float *bf, float *dz, float *loss_n, float *dPq, hipStream_t st);
@@ -115,7 +118,7 @@ hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStre
 // is given; the batch-mean loss when loss_out is given
 hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,
                            const float *U, const float *dPq, float *dU, const float *Wa, float *WaT, int R, int S,
-                           int K, const float *loss_n, float *loss_out, hipStream_t st);
+                           int K, const float *loss_n, float *loss_out, const int32_t *parg, hipStream_t st);
 
 // ---- elementwise / data movement ----
 hipError_t launch_maxpool_fwd(const float *T, float *Y, uint8_t *arg, int B, int Ho, int Wo, int K, int Hp,

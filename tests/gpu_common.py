@@ -32,10 +32,11 @@ def to_dev(a):
     return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def descs(spec, n_classes, relu=1):
+def descs(spec, n_classes, relu=1, head_pool=0, loss_kind=0):
     lf = spec.layer_desc_fields()
     af = spec.aux_desc_fields(n_classes)
     af["relu"] = relu
+    af["head_pool"], af["loss_kind"] = head_pool, loss_kind
     return (nf.LayerDesc(**lf), nf.AuxDesc(**af)), (O.layer_desc(**lf), O.aux_desc(**af))
 
 
@@ -52,8 +53,8 @@ def make_inputs(spec, B, n_classes, seed, bias_std=0.1, post_relu_input=False):
     return x, xs, labels, p
 
 
-def gpu_layer(spec, n_classes, p, B, momentum, relu=1):
-    (d, a), _ = descs(spec, n_classes, relu)
+def gpu_layer(spec, n_classes, p, B, momentum, relu=1, head_pool=0, loss_kind=0):
+    (d, a), _ = descs(spec, n_classes, relu, head_pool, loss_kind)
     return LocalLayer(d, a, layout.params_to_lib(p, spec.A), B, momentum)
 
 
@@ -78,14 +79,19 @@ def gpu_decisions(L, spec, B, y_gpu):
         hh, ww = ii + u, jj + v
         assert hh.min() >= 0 and hh.max() < spec.Ho and ww.min() >= 0 and ww.max() < spec.Wo, "arg-max outside the map"
         arg = (hh * spec.Wo + ww).astype(np.int32)
-    return mask_u, layout.act_from_lib(y_gpu), arg
+    parg = None
+    if L.a.head_pool == 1:
+        off, nb = nf.nf_workspace_region(L.d, L.a, B, nf.NF_WS_HEAD_ARG)
+        pa = ws[off:off + nb].view(torch.int32).view(B, L.a.pool_oh, L.a.pool_ow, spec.A).cpu().numpy()
+        parg = np.ascontiguousarray(pa.transpose(0, 3, 1, 2)).reshape(B, -1)  # oracle's (a, i, j) order
+    return mask_u, layout.act_from_lib(y_gpu), arg, parg
 
 
 def oracle_step(od, oa, spec, x, xs, labels, po, mo, lr, mu, dec):
     """One local step of the oracle (forward, head, loss, gradients, update in place), taking the
     ReLU / max-pool decisions from `dec` (the kernels') wherever the oracle's own pre-activation
     is a tie; anywhere else the two must agree, which is asserted."""
-    mask_u_gpu, y_gpu, arg_gpu = dec
+    mask_u_gpu, y_gpu, arg_gpu, parg_gpu = dec
     lf = O.layer_fwd(od, x, xs, po["W"], po["b"], po["Wp"])
     af = O.aux_fwd_loss(oa, lf.Y, labels, po["Wa"], po["ba"], po["Wf"], po["bf"])
     tol_z = TIE * np.abs(lf.Z).max()
@@ -119,6 +125,22 @@ def oracle_step(od, oa, spec, x, xs, labels, po, mo, lr, mu, dec):
         assert np.all(np.abs(af.Upre[diff]) <= TIE * np.abs(af.Upre).max()), "aux ReLU decision differs away from a tie"
         n_tie += int(diff.sum())
         mask_u = mask_u_gpu
+    if oa.head_pool == 1:
+        # the head's max-pooling selection: where the kernels picked another element, the two
+        # candidates must be equal to within rounding
+        Bn, A = af.U.shape[0], af.U.shape[1]
+        assert parg_gpu.min() >= 0 and parg_gpu.max() < af.U.shape[2] * af.U.shape[3], "selection outside the map"
+        flatU = np.repeat(af.U.reshape(Bn, A, 1, -1), oa.pool_oh * oa.pool_ow, axis=2).reshape(Bn, af.parg.shape[1], -1)
+        picked = np.take_along_axis(flatU, parg_gpu[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+        Hu, Wu, oh, ow = af.U.shape[2], af.U.shape[3], oa.pool_oh, oa.pool_ow
+        fi, fj = (np.arange(af.parg.shape[1]) % (oh * ow)) // ow, np.arange(af.parg.shape[1]) % ow
+        hh, ww = parg_gpu // Wu, parg_gpu % Wu
+        inside = ((hh >= fi * Hu // oh) & (hh < -(-(fi + 1) * Hu // oh)) &
+                  (ww >= fj * Wu // ow) & (ww < -(-(fj + 1) * Wu // ow)))
+        assert inside.all(), "head max-pool selection outside its window"
+        assert np.all(picked >= af.Pq - TIE * np.abs(af.U).max()), "head max-pool selection differs away from a tie"
+        n_tie += int((parg_gpu != af.parg).sum())
+        af.parg = parg_gpu.astype(np.int32)
     lf = O.LayerFwd(lf.Z, lf.Y, arg)
     g = O.local_bwd(od, oa, x, xs, lf, af, po["Wa"], po["Wf"], mask_u=mask_u, mask_z=mask_z)
     for k in PARAM_NAMES:
@@ -127,12 +149,12 @@ def oracle_step(od, oa, spec, x, xs, labels, po, mo, lr, mu, dec):
     return lf.Y, af.loss, g, n_tie
 
 
-def run_step_both(spec, n_classes, B, seed, lr, mu, steps=1, relu=1, bias_std=0.1):
+def run_step_both(spec, n_classes, B, seed, lr, mu, steps=1, relu=1, bias_std=0.1, head_pool=0, loss_kind=0):
     """Runs `steps` local steps on the same batch through the library and the oracle; returns
     per-step (loss, grads, y) for both and the final params/momentum for both."""
     x, xs, labels, p = make_inputs(spec, B, n_classes, seed, bias_std)
-    (_, _), (od, oa) = descs(spec, n_classes, relu)
-    L = gpu_layer(spec, n_classes, p, B, mu != 0, relu)
+    (_, _), (od, oa) = descs(spec, n_classes, relu, head_pool, loss_kind)
+    L = gpu_layer(spec, n_classes, p, B, mu != 0, relu, head_pool, loss_kind)
     xd, xsd, ld = to_dev(layout.act_to_lib(x)), to_dev(None if xs is None else layout.act_to_lib(xs)), to_dev(labels)
     po = {k: (None if v is None else v.copy()) for k, v in p.items()}
     mo = {k: (None if v is None else np.zeros_like(v)) for k, v in p.items()} if mu != 0 else None

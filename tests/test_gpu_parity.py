@@ -63,6 +63,23 @@ def test_local_step_matches_oracle(name):
     G.check_step_results(name, out, final)
 
 
+VARIANTS = {"maxpool_ce": (1, 0), "avgpool_mse": (0, 1), "maxpool_mse": (1, 1)}
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("name", ["ragged_small", "scalar_paths_c3_k6_a5", "pool2", "odd_3x3_overlapping_avg_windows",
+                                  "emits_1x1", "head_a32_n64", "n160_two_tiles_a80", "skinny_a4_c256_split",
+                                  "skinny_a12_c136_ragged"])
+def test_head_variants_match_oracle(name, variant):
+    """Max pooling as the head's down-sampling F_n and mean squared error as the loss (the
+    alternatives the paper names next to average pooling and cross-entropy)."""
+    spec, B, cls = CASES[name]
+    hp, lk = VARIANTS[variant]
+    print(f"case {name} {variant}: B={B}", flush=True)
+    out, final = G.run_step_both(spec, cls, B, seed=102, lr=0.05, mu=0.9, steps=2, head_pool=hp, loss_kind=lk)
+    G.check_step_results(f"{name}/{variant}", out, final)
+
+
 def test_local_step_no_relu_head_no_momentum():
     spec, B, cls = CASES["pool2"]
     out, final = G.run_step_both(spec, cls, B, seed=101, lr=0.01, mu=0.0, steps=2, relu=0)
