@@ -217,6 +217,29 @@ int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, con
                             int32_t *labels_out, int64_t capacity_out, void *ws, size_t ws_bytes,
                             void *stream);
 
+/* ---- Profiler and Partitioner ("Modules", Algorithm 1): host functions, no device work ---------
+ * The Profiler's measured memory is replaced by the exact device bytes of one local step with
+ * this library: parameters + gradients (+ momentum buffers) of the layer and its head, the input,
+ * shortcut and emitted batches, labels, and nf_workspace_bytes.  nf_fit_linear is the Profiler's
+ * linear model (least squares: bytes ~ intercept + slope * batch); nf_profile_layer evaluates the
+ * byte count at n (2..64) batch sizes and fits it.  nf_partition is Algorithm 1: per layer the
+ * largest batch size whose model stays within the budget M (same unit as the models), capped at
+ * B_limit; then consecutive layers are grouped into one block while
+ * |b[i+1] - b[i]| <= rho * b[i], a block taking the smallest batch size of its layers.
+ * Outputs: layer_batch[n_layers] (optional), block_first[k] = index of the first layer of block
+ * k and block_batch[k] (arrays of n_layers entries), *n_blocks.  A layer that does not fit at
+ * batch size 1 gets batch size 0. */
+typedef struct {
+  double slope, intercept;
+} nf_linear_model;
+int32_t nf_layer_step_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, int32_t with_momentum,
+                            size_t *out);
+int32_t nf_fit_linear(int32_t n, const double *batch, const double *bytes, nf_linear_model *out);
+int32_t nf_profile_layer(const nf_layer_desc *d, const nf_aux_desc *a, int32_t with_momentum, int32_t n,
+                         const int32_t *batches, nf_linear_model *out);
+int32_t nf_partition(int32_t n_layers, const nf_linear_model *R, double M, int32_t B_limit, double rho,
+                     int32_t *layer_batch, int32_t *block_first, int32_t *block_batch, int32_t *n_blocks);
+
 /* ---- measurement aid (not a step of the method) ---------------------------------------------
  * Between nf_prof_begin and nf_prof_end every kernel the library enqueues is bracketed by a
  * HIP-event pair on the caller's stream.  nf_prof_end waits for those events (the only call

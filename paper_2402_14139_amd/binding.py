@@ -20,7 +20,8 @@ NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
-           "nf_block_train_epoch", "nf_block_fill_cache")
+           "nf_block_train_epoch", "nf_block_fill_cache", "nf_layer_step_bytes", "nf_fit_linear",
+           "nf_profile_layer", "nf_partition")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
 NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
@@ -61,6 +62,10 @@ class ProfRecord(C.Structure):
 
 class AuxParams(C.Structure):
     _fields_ = [("Wa", C.c_void_p), ("ba", C.c_void_p), ("Wf", C.c_void_p), ("bf", C.c_void_p)]
+
+
+class LinearModel(C.Structure):
+    _fields_ = [("slope", C.c_double), ("intercept", C.c_double)]
 
 
 class Block(C.Structure):
@@ -116,6 +121,14 @@ def lib():
                                            C.c_void_p, C.c_void_p]
         L.nf_block_fill_cache.argtypes = [C.POINTER(Block), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_layer_step_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
+                                          C.POINTER(C.c_size_t)]
+        L.nf_fit_linear.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(LinearModel)]
+        L.nf_profile_layer.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
+                                       C.POINTER(C.c_int32), C.POINTER(LinearModel)]
+        L.nf_partition.argtypes = [C.c_int32, C.POINTER(LinearModel), C.c_double, C.c_int32, C.c_double,
+                                   C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -290,3 +303,34 @@ def nf_block_fill_cache(blk: Block, B, n_items, cache_in, labels_in, capacity_in
     _check(lib().nf_block_fill_cache(C.byref(blk), B, n_items, _ptr(cache_in), _ptr(labels_in), capacity_in,
                                      _ptr(cache_out), _ptr(labels_out), capacity_out, wp, wn, _stream(stream)),
            "nf_block_fill_cache")
+
+
+def nf_layer_step_bytes(d: LayerDesc, a: AuxDesc, B: int, with_momentum: bool) -> int:
+    out = C.c_size_t()
+    _check(lib().nf_layer_step_bytes(C.byref(d), C.byref(a), B, int(with_momentum), C.byref(out)),
+           "nf_layer_step_bytes")
+    return int(out.value)
+
+
+def nf_fit_linear(batches, nbytes):
+    n = len(batches)
+    m = LinearModel()
+    _check(lib().nf_fit_linear(n, (C.c_double * n)(*batches), (C.c_double * n)(*nbytes), C.byref(m)), "nf_fit_linear")
+    return m.slope, m.intercept
+
+
+def nf_profile_layer(d: LayerDesc, a: AuxDesc, with_momentum: bool, batches):
+    n = len(batches)
+    m = LinearModel()
+    _check(lib().nf_profile_layer(C.byref(d), C.byref(a), int(with_momentum), n, (C.c_int32 * n)(*batches),
+                                  C.byref(m)), "nf_profile_layer")
+    return m.slope, m.intercept
+
+
+def nf_partition(models, M: float, B_limit: int, rho: float):
+    """models: list of (slope, intercept).  Returns (per-layer batch sizes, [(first layer, batch size), ...])."""
+    n = len(models)
+    R = (LinearModel * n)(*[LinearModel(s, c) for s, c in models])
+    lb, bf, bb, nb = (C.c_int32 * n)(), (C.c_int32 * n)(), (C.c_int32 * n)(), C.c_int32()
+    _check(lib().nf_partition(n, R, M, B_limit, rho, lb, bf, bb, C.byref(nb)), "nf_partition")
+    return list(lb), [(int(bf[k]), int(bb[k])) for k in range(nb.value)]

@@ -1,0 +1,101 @@
+// Profiler and Partitioner of NeuroFlux (arXiv 2402.14139, "Modules", Algorithm 1) as host
+// functions of libnf (include/nf.h).  No device work: the Profiler's measurements are replaced by
+// the exact number of device bytes one local step of a layer needs with this library (the caller
+// owns every buffer, so the figure is known without running anything), its linear models are
+// least-squares lines through that figure at the given batch sizes, and Algorithm 1 groups the
+// layers into blocks from those models.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+
+#include "../../include/nf.h"
+
+extern "C" {
+
+int32_t nf_layer_step_bytes(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, int32_t with_momentum,
+                            size_t *out) {
+  if (!d || !a || !out) return NF_ERR_NULL;
+  size_t ws = 0;
+  int32_t rc = nf_workspace_bytes(d, a, B, &ws);
+  if (rc) return rc;
+  int32_t Hp = 0, Wp = 0;
+  if ((rc = nf_layer_out_dims(d, nullptr, nullptr, &Hp, &Wp))) return rc;
+  const size_t f = sizeof(float);
+  // parameters of theta_n, beta_n, gamma_n; their gradients; optionally their momentum buffers
+  size_t params = (size_t)d->C_out * d->R * d->S * d->C_in + d->C_out;
+  if (d->skip_kind == 2) params += (size_t)d->C_out * d->skip_C;
+  const size_t F = (size_t)a->A * a->pool_oh * a->pool_ow;
+  params += (size_t)a->A * a->R * a->S * a->C_in + a->A + (size_t)a->n_classes * F + a->n_classes;
+  const size_t fixed = params * f * (with_momentum ? 3 : 2);
+  // per batch: input, shortcut input, emitted activation, labels, the loss scalar, workspace
+  size_t act = (size_t)B * d->C_in * d->H_in * d->W_in + (size_t)B * d->C_out * Hp * Wp;
+  if (d->skip_kind) act += (size_t)B * d->skip_C * d->skip_H * d->skip_W;
+  *out = fixed + act * f + (size_t)B * sizeof(int32_t) + f + ws;
+  return NF_OK;
+}
+
+int32_t nf_fit_linear(int32_t n, const double *batch, const double *bytes, nf_linear_model *out) {
+  if (!batch || !bytes || !out) return NF_ERR_NULL;
+  if (n < 2) return NF_ERR_BAD_DESC;
+  double sx = 0, sy = 0, sxx = 0, sxy = 0;
+  for (int i = 0; i < n; ++i) sx += batch[i], sy += bytes[i], sxx += batch[i] * batch[i], sxy += batch[i] * bytes[i];
+  const double den = n * sxx - sx * sx;
+  if (!(den > 0)) return NF_ERR_BAD_DESC;  // all batch sizes equal
+  out->slope = (n * sxy - sx * sy) / den;
+  out->intercept = (sy - out->slope * sx) / n;
+  return NF_OK;
+}
+
+int32_t nf_profile_layer(const nf_layer_desc *d, const nf_aux_desc *a, int32_t with_momentum, int32_t n,
+                         const int32_t *batches, nf_linear_model *out) {
+  if (!batches || !out) return NF_ERR_NULL;
+  if (n < 2 || n > 64) return NF_ERR_BAD_DESC;
+  double x[64], y[64];
+  for (int i = 0; i < n; ++i) {
+    size_t bytes = 0;
+    const int32_t rc = nf_layer_step_bytes(d, a, batches[i], with_momentum, &bytes);
+    if (rc) return rc;
+    x[i] = (double)batches[i], y[i] = (double)bytes;
+  }
+  return nf_fit_linear(n, x, y, out);
+}
+
+int32_t nf_partition(int32_t n_layers, const nf_linear_model *R, double M, int32_t B_limit, double rho,
+                     int32_t *layer_batch, int32_t *block_first, int32_t *block_batch, int32_t *n_blocks) {
+  if (!R || !block_first || !block_batch || !n_blocks) return NF_ERR_NULL;
+  if (n_layers <= 0 || B_limit <= 0 || !(rho >= 0) || !(M >= 0)) return NF_ERR_BAD_DESC;
+  int32_t *b = layer_batch;
+  int32_t *own = nullptr;
+  if (!b) {
+    own = static_cast<int32_t *>(std::malloc(sizeof(int32_t) * (size_t)n_layers));
+    if (!own) return NF_ERR_DEVICE;
+    b = own;
+  }
+  // first loop of Algorithm 1: largest batch size within the budget, capped at the limit
+  for (int l = 0; l < n_layers; ++l) {
+    double t;
+    if (R[l].slope > 0)
+      t = std::floor((M - R[l].intercept) / R[l].slope + 1e-12);
+    else
+      t = R[l].intercept <= M ? (double)B_limit : 0.0;
+    t = std::max(0.0, std::min(t, (double)B_limit));
+    b[l] = (int32_t)t;
+  }
+  // second loop: a block grows while consecutive layers' batch sizes stay within rho of each other
+  int nb = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    block_first[nb] = i;
+    int32_t batch = b[i];
+    while (i + 1 < n_layers && std::fabs((double)b[i + 1] - (double)b[i]) <= rho * (double)b[i]) {
+      batch = std::min(batch, b[i + 1]);
+      ++i;
+    }
+    block_batch[nb++] = batch;
+  }
+  *n_blocks = nb;
+  std::free(own);
+  return NF_OK;
+}
+
+}  // extern "C"

@@ -99,3 +99,106 @@ def test_max_batch_and_partition_end_to_end():
     assert b[0] == 36 and b == sorted(b) and b[-1] == 512          # 630 / 17.19 = 36.6
     assert blocks == _closed_form(b, 0.4)
     assert blocks[0][1] == 36 and blocks[-1][1] == 512
+
+
+# ---- the library's host functions (C ABI, no device work) against the oracle --------------------
+@pytest.fixture(scope="module")
+def nf():
+    from paper_2402_14139_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2402_14139_amd import build
+        build.build()
+    binding.lib()
+    return binding
+
+
+def test_library_fit_and_partition_match_oracle(nf):
+    r = _rows("fig5_memory_vs_batch_vgg11.txt")
+    x = [float(v) for v in r["batch"]]
+    models = []
+    for i in range(1, 9):
+        y = [float(v) for v in r[f"L{i}"]]
+        s, c = nf.nf_fit_linear(x, y)
+        os_, oc = OP.fit_linear(x, y)
+        assert abs(s - os_) <= 1e-12 * abs(os_) and abs(c - oc) <= 1e-9 * max(1.0, abs(oc))
+        models.append((s, c))
+    for M in (100.0, 630.0, 4000.0):
+        for rho in (0.0, 0.4, 0.7):
+            b, blocks = nf.nf_partition(models, M, 512, rho)
+            ob, oblocks = OP.partition(models, M, 512, rho)
+            assert b == ob and blocks == [(ls[0], bs) for ls, bs in oblocks], (M, rho)
+    # the paper's printed per-layer maximum batch sizes: models with slope 1, intercept 0 and a
+    # budget of t reproduce t
+    t = [int(v) for v in _rows("fig6_max_batch_vgg19.txt")["max_batch"]]
+    got = []
+    for ti in t:
+        b, _ = nf.nf_partition([(1.0, 0.0)], float(ti), 512, 0.4)
+        got.append(b[0])
+    assert got == [min(v, 512) for v in t]
+    lm = [(630.0 / (v + 0.5), 0.0) for v in t]            # each layer fits exactly t[v] samples in 630
+    b, blocks = nf.nf_partition(lm, 630.0, 512, 0.4)
+    assert b == [min(v, 512) for v in t]
+    assert [(f + 1, bs) for f, bs in blocks] == [(1, 30), (4, 60), (5, 90), (9, 195), (13, 512)]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_library_partition_random(nf, seed):
+    g = np.random.default_rng(100 + seed)
+    n = int(g.integers(1, 50))
+    models = [(float(g.uniform(0.05, 40)), float(g.uniform(0, 200))) for _ in range(n)]
+    M, B, rho = float(g.uniform(100, 5000)), int(g.integers(1, 1024)), float(g.choice([0.0, 0.2, 0.4, 1.0]))
+    b, blocks = nf.nf_partition(models, M, B, rho)
+    ob, oblocks = OP.partition(models, M, B, rho)
+    assert b == ob and blocks == [(ls[0], bs) for ls, bs in oblocks]
+
+
+def test_library_byte_model_and_profile(nf):
+    """The byte count is what a caller really allocates for one local step: checked against a
+    plain sum over the tensors of the step; it is affine in B apart from the alignment and split
+    choices of the workspace (split-reduction partials), so the fitted line predicts it only to within 25 %; Algorithm 1
+    on the ResNet-18-style network under 256 MiB yields non-decreasing block batch sizes."""
+    import workloads
+    cfg = workloads.config("cfg3")
+    models = []
+    for ls in cfg.layers:
+        d, a = nf.LayerDesc(**ls.layer_desc_fields()), nf.AuxDesc(**ls.aux_desc_fields(cfg.n_classes))
+        for B in (8, 64):
+            got = nf.nf_layer_step_bytes(d, a, B, True)
+            params = ls.C_out * ls.C_in * ls.R * ls.S + ls.C_out + (ls.C_out * ls.skip_C if ls.skip_kind == 2 else 0)
+            params += ls.A * 9 * ls.C_out + ls.A + cfg.n_classes * 4 * ls.A + cfg.n_classes
+            act = B * (ls.C_in * ls.H_in * ls.W_in + ls.C_out * ls.Hp * ls.Wp
+                       + (ls.skip_C * ls.skip_H * ls.skip_W if ls.skip_kind else 0))
+            want = 4 * (3 * params + act) + 4 * B + 4 + nf.nf_workspace_bytes(d, a, B)
+            assert got == want
+            assert nf.nf_layer_step_bytes(d, a, B, False) == want - 4 * params
+        batches = [16, 32, 64, 128, 256]
+        s, c = nf.nf_profile_layer(d, a, True, batches)
+        os_, oc = OP.fit_linear(batches, [nf.nf_layer_step_bytes(d, a, B, True) for B in batches])
+        assert abs(s - os_) <= 1e-9 * os_ and abs(c - oc) <= 1e-6 * max(1.0, abs(oc))
+        for B in (48, 200):
+            exact = nf.nf_layer_step_bytes(d, a, B, True)
+            assert abs(s * B + c - exact) <= 0.25 * exact, (ls.name, B, s * B + c, exact)
+        models.append((s, c))
+    b, blocks = nf.nf_partition(models, float(256 << 20), 512, 0.4)
+    ob, oblocks = OP.partition(models, float(256 << 20), 512, 0.4)
+    assert b == ob and blocks == [(ls[0], bs) for ls, bs in oblocks]
+    sizes = [bs for _, bs in blocks]
+    assert sizes == sorted(sizes) and 0 < sizes[0] < sizes[-1] <= 512 and len(blocks) >= 2
+    print("cfg3 under 256 MiB:", b, blocks)
+
+
+def test_library_partition_rejects_bad_arguments(nf):
+    import ctypes as C
+    L = nf.lib()
+    R = (nf.LinearModel * 2)(nf.LinearModel(1.0, 0.0), nf.LinearModel(2.0, 0.0))
+    o = (C.c_int32 * 2)()
+    nb = C.c_int32()
+    assert L.nf_partition(2, None, 10.0, 8, 0.4, None, o, o, C.byref(nb)) == nf.NF_ERR_NULL
+    assert L.nf_partition(0, R, 10.0, 8, 0.4, None, o, o, C.byref(nb)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_partition(2, R, 10.0, 0, 0.4, None, o, o, C.byref(nb)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_partition(2, R, 10.0, 8, -0.1, None, o, o, C.byref(nb)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_partition(2, R, 10.0, 8, 0.4, None, o, o, C.byref(nb)) == nf.NF_OK and nb.value >= 1
+    m = nf.LinearModel()
+    x = (C.c_double * 2)(4.0, 4.0)
+    assert L.nf_fit_linear(2, x, x, C.byref(m)) == nf.NF_ERR_BAD_DESC      # equal batch sizes: no line
+    assert L.nf_fit_linear(1, x, x, C.byref(m)) == nf.NF_ERR_BAD_DESC
