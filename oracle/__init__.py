@@ -297,3 +297,52 @@ def block_fill_cache(layers, cache_in, labels_in, n_items, B, sample_shape, cach
             p = L.params
             inputs.append(layer_fwd(L.d, inputs[n], xs, p["W"], p["b"], p.get("Wp")).Y)
         cache_write(cache_out, labels_out, first, inputs[-1], lab)
+
+
+# ---- early-exit evaluation ("Trained Output CNN"): forward only, prediction, accuracy -----------
+def aux_predict(a: AuxDesc, y, Wa, ba, Wf, bf):
+    """Logits of the head on emitted activations ``y`` (Eq. 2) and the predicted class per
+    sample: the class with the largest logit, the lowest index among equal maxima."""
+    af = aux_fwd_loss(a, y, np.zeros((y.shape[0],), np.int32), Wa, ba, Wf, bf)
+    pred = np.empty((y.shape[0],), np.int32)
+    for n in range(y.shape[0]):
+        best, bi = af.z[n, 0], 0
+        for q in range(1, a.n_classes):
+            if af.z[n, q] > best:
+                best, bi = af.z[n, q], q
+        pred[n] = bi
+    return af.z, pred
+
+
+def block_evaluate(layers, exit_layer, cache, cache_labels, n_items, B, sample_shape):
+    """Early-exit model that leaves the block after layer ``exit_layer`` (0-based): forward
+    through layers 0..exit_layer with their current weights, then that layer's head; rows
+    [0, n_items) of the block's input cache in batches of B.  Returns (predictions [n_items],
+    number of correct predictions)."""
+    preds = np.empty((n_items,), np.int32)
+    correct = 0
+    for first, nb in _batches(n_items, B):
+        x0, lab = cache_read(cache, cache_labels, first, None, nb, sample_shape)
+        inputs = [x0]
+        for n in range(exit_layer + 1):
+            L = layers[n]
+            xs = None if L.skip_src < 0 else inputs[L.skip_src]
+            p = L.params
+            inputs.append(layer_fwd(L.d, inputs[n], xs, p["W"], p["b"], p.get("Wp")).Y)
+        p = layers[exit_layer].params
+        _, pr = aux_predict(layers[exit_layer].a, inputs[-1], p["Wa"], p["ba"], p["Wf"], p["bf"])
+        preds[first:first + nb] = pr
+        correct += int((pr == lab).sum())
+    return preds, correct
+
+
+def select_exit(n_correct, n_params):
+    """The output model: the exit with the highest validation accuracy; among equally accurate
+    exits the one with the fewest parameters; among those the earliest.  ``n_correct[e]`` is the
+    number of correct validation predictions of exit e, ``n_params[e]`` the parameter count of
+    the model that ends there.  Returns the exit's index."""
+    best = 0
+    for e in range(1, len(n_correct)):
+        if n_correct[e] > n_correct[best] or (n_correct[e] == n_correct[best] and n_params[e] < n_params[best]):
+            best = e
+    return best

@@ -668,3 +668,70 @@ def test_variant_closed_forms(oracle):
     af0 = o.aux_fwd_loss(a0, lf.Y, labels[:1], Wa * 0, -np.abs(ba) - 1, Wf, bf)
     gr = o.local_bwd(d0, a0, x0, None, lf, af0, Wa * 0, Wf)
     assert not gr["Wa"].any() and not gr["W"].any() and gr["Wf"].shape == (Cls, 8)
+
+
+# ---- early-exit evaluation: prediction and accuracy ---------------------------------------------
+def test_prediction_closed_forms_and_torch(oracle):
+    import torch
+    import torch.nn.functional as F
+    o = oracle
+    g = workloads.rng_for(8, "predict")
+    B, Cls = 9, 5
+    y = np.abs(g.standard_normal((B, 3, 6, 6)))
+    Wa, ba = g.standard_normal((2, 3, 3, 3)), g.standard_normal((2,))
+    Wf, bf = g.standard_normal((Cls, 8)), g.standard_normal((Cls,))
+    a = o.aux_desc(3, 6, 6, 2, Cls)
+    z, pred = o.aux_predict(a, y, Wa, ba, Wf, bf)
+    # library pin: the head through torch
+    u = torch.relu(F.conv2d(torch.tensor(y), torch.tensor(Wa), torch.tensor(ba), padding=1))
+    zt = F.linear(F.adaptive_avg_pool2d(u, (2, 2)).flatten(1), torch.tensor(Wf), torch.tensor(bf))
+    np.testing.assert_allclose(z, zt.numpy(), rtol=1e-12, atol=1e-13)
+    assert np.array_equal(pred, zt.argmax(1).numpy())
+    # zero linear weights: the bias alone decides -> every sample gets argmax(bf)
+    _, p0 = o.aux_predict(a, y, Wa, ba, Wf * 0, bf)
+    assert np.all(p0 == int(np.argmax(bf)))
+    # all logits equal: the lowest class index
+    _, p1 = o.aux_predict(a, y, Wa, ba, Wf * 0, bf * 0 + 0.25)
+    assert np.all(p1 == 0)
+    # two equal maxima: the lower index of the two
+    b2 = np.array([0.0, 3.0, -1.0, 3.0, 1.0])
+    _, p2 = o.aux_predict(a, y, Wa, ba, Wf * 0, b2)
+    assert np.all(p2 == 1)
+    # relabelling the classes relabels the predictions
+    perm = np.array([3, 0, 4, 1, 2])
+    _, pp = o.aux_predict(a, y, Wa, ba, Wf[perm], bf[perm])
+    assert np.array_equal(perm[pp], pred)
+
+
+def test_block_evaluate_and_exit_selection(oracle):
+    import torch
+    import torch.nn.functional as F
+    o = oracle
+    specs, layers = _block(o, "basic")
+    N, Cls = 11, 3
+    g = workloads.rng_for(9, "block-eval")
+    X = g.standard_normal((N, 2, 8, 8))
+    lab = g.integers(0, Cls, size=(N,)).astype(np.int32)
+    bl = _as_block_layers(o, layers, 0.0)
+    counts = []
+    for e in range(3):
+        preds, correct = o.block_evaluate(bl, e, X.reshape(N, -1).copy(), lab, N, 4, X.shape[1:])
+        feats = torch.tensor(torch_ref.block_forward(layers[:e + 1], X))
+        d, a, p, _ = layers[e]
+        u = torch.relu(F.conv2d(feats, torch.tensor(p["Wa"]), torch.tensor(p["ba"]), padding=1))
+        zt = F.linear(F.adaptive_avg_pool2d(u, (2, 2)).flatten(1), torch.tensor(p["Wf"]), torch.tensor(p["bf"]))
+        assert np.array_equal(preds, zt.argmax(1).numpy().astype(np.int32))
+        assert correct == int((preds == lab).sum())
+        counts.append(correct)
+    # a head that always answers class c is right exactly on the samples labelled c
+    for L in bl:
+        L.params["Wf"][:] = 0
+        L.params["bf"][:] = np.array([0.0, 1.0, 0.5])
+    preds, correct = o.block_evaluate(bl, 1, X.reshape(N, -1).copy(), lab, N, 5, X.shape[1:])
+    assert np.all(preds == 1) and correct == int((lab == 1).sum())
+    # exit selection: highest accuracy; ties -> fewest parameters; then the earliest
+    assert o.select_exit([5, 9, 9, 7], [10, 20, 30, 40]) == 1
+    assert o.select_exit([5, 9, 9, 7], [10, 30, 20, 40]) == 2
+    assert o.select_exit([9, 9, 9], [10, 10, 10]) == 0
+    assert o.select_exit([1, 2, 3], [10, 20, 30]) == 2
+    assert 0 <= o.select_exit(counts, [1, 2, 3]) < 3
