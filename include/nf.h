@@ -217,6 +217,26 @@ int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, con
                             int32_t *labels_out, int64_t capacity_out, void *ws, size_t ws_bytes,
                             void *stream);
 
+/* ---- early-exit evaluation ("Trained Output CNN") ---------------------------------------------
+ * nf_aux_predict: forward of the head only on emitted activations y [B,Hp,Wp,C_out]; pred_out
+ * (device int32 [B]) receives the class with the largest logit (lowest index among equal maxima);
+ * with labels, *n_correct (device int32) receives the number of correct predictions of the batch,
+ * added to its previous value when accumulate != 0 (labels and n_correct are given together or
+ * both NULL); logits_out (device [B][n_classes]) is optional.
+ * nf_block_evaluate: the early-exit model that leaves the block after layer exit_layer: rows
+ * [0, n_items) of the block's input cache in batches of B (last one partial), forward through
+ * layers 0..exit_layer, that layer's head; pred_out [n_items], *n_correct the total.  The block's
+ * aux and ap arrays are required, gp/ga/vp/va are not read.
+ * nf_select_exit (host): index of the exit with the most correct validation predictions; among
+ * equals the one whose model has the fewest parameters; among those the earliest. */
+int32_t nf_aux_predict(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *y,
+                       const int32_t *labels, const nf_aux_params *ap, int32_t *pred_out, int32_t *n_correct,
+                       int32_t accumulate, float *logits_out, void *ws, size_t ws_bytes, void *stream);
+int32_t nf_block_evaluate(const nf_block *blk, int32_t exit_layer, int32_t B, int64_t n_items,
+                          const float *cache, const int32_t *cache_labels, int64_t capacity,
+                          int32_t *pred_out, int32_t *n_correct, void *ws, size_t ws_bytes, void *stream);
+int32_t nf_select_exit(int32_t n_exits, const int64_t *n_correct, const int64_t *n_params, int32_t *exit_out);
+
 /* ---- Profiler and Partitioner ("Modules", Algorithm 1): host functions, no device work ---------
  * The Profiler's measured memory is replaced by the exact device bytes of one local step with
  * this library: parameters + gradients (+ momentum buffers) of the layer and its head, the input,

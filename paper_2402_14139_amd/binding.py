@@ -21,7 +21,7 @@ EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_f
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
            "nf_block_train_epoch", "nf_block_fill_cache", "nf_layer_step_bytes", "nf_fit_linear",
-           "nf_profile_layer", "nf_partition")
+           "nf_profile_layer", "nf_partition", "nf_aux_predict", "nf_block_evaluate", "nf_select_exit")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
 NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
@@ -121,6 +121,12 @@ def lib():
                                            C.c_void_p, C.c_void_p]
         L.nf_block_fill_cache.argtypes = [C.POINTER(Block), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_aux_predict.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.POINTER(AuxParams), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.c_size_t, C.c_void_p]
+        L.nf_block_evaluate.argtypes = [C.POINTER(Block), C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_select_exit.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.nf_layer_step_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
                                           C.POINTER(C.c_size_t)]
         L.nf_fit_linear.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(LinearModel)]
@@ -334,3 +340,25 @@ def nf_partition(models, M: float, B_limit: int, rho: float):
     lb, bf, bb, nb = (C.c_int32 * n)(), (C.c_int32 * n)(), (C.c_int32 * n)(), C.c_int32()
     _check(lib().nf_partition(n, R, M, B_limit, rho, lb, bf, bb, C.byref(nb)), "nf_partition")
     return list(lb), [(int(bf[k]), int(bb[k])) for k in range(nb.value)]
+
+
+def nf_aux_predict(d, a, B, y, labels, ap: AuxParams, pred_out, n_correct, accumulate, logits_out, ws, stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().nf_aux_predict(C.byref(d), C.byref(a), B, _ptr(y), _ptr(labels), C.byref(ap), _ptr(pred_out),
+                                _ptr(n_correct), int(accumulate), _ptr(logits_out), wp, wn, _stream(stream)),
+           "nf_aux_predict")
+
+
+def nf_block_evaluate(blk: Block, exit_layer, B, n_items, cache, cache_labels, capacity, pred_out, n_correct, ws,
+                      stream=None):
+    wp, wn = _ws(ws)
+    _check(lib().nf_block_evaluate(C.byref(blk), exit_layer, B, n_items, _ptr(cache), _ptr(cache_labels), capacity,
+                                   _ptr(pred_out), _ptr(n_correct), wp, wn, _stream(stream)), "nf_block_evaluate")
+
+
+def nf_select_exit(n_correct, n_params) -> int:
+    n = len(n_correct)
+    out = C.c_int32()
+    _check(lib().nf_select_exit(n, (C.c_int64 * n)(*n_correct), (C.c_int64 * n)(*n_params), C.byref(out)),
+           "nf_select_exit")
+    return int(out.value)

@@ -332,6 +332,70 @@ __global__ __launch_bounds__(WT) void head_fc_wide_kernel(HeadShape s, const flo
   }
 }
 
+// Forward-only head for early-exit evaluation: one sample per workgroup; logits with one
+// wavefront per class (lanes stride the features), then the arg-max over the classes with the
+// lowest index winning among equal maxima.  Dynamic LDS: F + Cls floats.
+__global__ __launch_bounds__(HT) void head_predict_kernel(HeadShape s, const float *__restrict__ Pq,
+                                                          const int32_t *__restrict__ labels,
+                                                          const float *__restrict__ Wf,
+                                                          const float *__restrict__ bf,
+                                                          float *__restrict__ logits_out, int32_t *__restrict__ pred,
+                                                          int32_t *__restrict__ hit) {
+  extern __shared__ float sm[];
+  __shared__ float rv[HT];
+  __shared__ int ri[HT];
+  float *pq = sm;          // [F]
+  float *z = pq + s.F;     // [Cls]
+  const int n = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
+  __syncthreads();
+  for (int q = wave; q < s.Cls; q += HT / 64) {
+    const float *wr = Wf + (long long)q * s.F;
+    float acc = 0.f;
+    for (int f = lane; f < s.F; f += 64) acc += wr[f] * pq[f];
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      const float v = acc + (bf ? bf[q] : 0.f);
+      z[q] = v;
+      if (logits_out) logits_out[(long long)n * s.Cls + q] = v;
+    }
+  }
+  __syncthreads();
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int q = t; q < s.Cls; q += HT)
+    if (z[q] > best) best = z[q], bi = q;  // ascending q, strict: lowest index of this thread's maxima
+  rv[t] = best, ri[t] = bi;
+  __syncthreads();
+  for (int o = HT / 2; o > 0; o >>= 1) {
+    if (t < o) {
+      const float cv = rv[t + o];
+      const int ci = ri[t + o];
+      if (cv > rv[t] || (cv == rv[t] && ci < ri[t])) rv[t] = cv, ri[t] = ci;
+    }
+    __syncthreads();
+  }
+  if (t == 0) {
+    const int p = ri[0] == 0x7fffffff ? 0 : ri[0];  // no logit compared greater than -inf (all NaN): class 0
+    pred[n] = p;
+    if (labels) hit[n] = p == labels[n] ? 1 : 0;
+  }
+}
+
+__global__ __launch_bounds__(HT) void count_hits_kernel(const int32_t *__restrict__ hit, int B,
+                                                        int32_t *__restrict__ out, int accumulate) {
+  __shared__ int red[HT];
+  int acc = 0;
+  for (int i = threadIdx.x; i < B; i += HT) acc += hit[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = HT / 2; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = (accumulate ? *out : 0) + red[0];
+}
+
 // batch mean of the per-sample losses, fixed order (one workgroup)
 __device__ inline void loss_mean_block(const float *__restrict__ loss_n, int B, float *__restrict__ out, float *red) {
   float acc = 0.f;
@@ -512,6 +576,18 @@ hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *la
   }
   const size_t lds = (size_t)(h.F + h.Cls + 8) * sizeof(float);
   hipLaunchKernelGGL(head_fc_kernel, dim3(h.B), dim3(HT), lds, st, h, Pq, labels, Wf, bf, dz, loss_n, dPq);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_predict(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
+                               const float *bf, float *logits_out, int32_t *pred, int32_t *hit, hipStream_t st) {
+  const size_t lds = (size_t)(h.F + h.Cls) * sizeof(float);
+  hipLaunchKernelGGL(head_predict_kernel, dim3(h.B), dim3(HT), lds, st, h, Pq, labels, Wf, bf, logits_out, pred, hit);
+  return hipGetLastError();
+}
+
+hipError_t launch_count_hits(const int32_t *hit, int B, int32_t *out, bool accumulate, hipStream_t st) {
+  hipLaunchKernelGGL(count_hits_kernel, dim3(1), dim3(HT), 0, st, hit, B, out, accumulate ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -292,9 +292,10 @@ HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
   return h;
 }
 
-// loss_out == nullptr: the batch mean is left to the backward launch that follows (run_bwd)
-int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const int32_t *labels,
-                    const nf_aux_params *ap, float *loss_out, void *ws, const WsLayout &w, hipStream_t st) {
+// beta_n and F_n of Eq. 2: the head's convolution (+ bias, ReLU) and its pooling; leaves U and Pq
+// (and the max-pooling selection) in the workspace
+int32_t run_aux_features(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const nf_aux_params *ap,
+                         void *ws, const WsLayout &w, hipStream_t st) {
   FwdProblem f;
   std::memset((void *)&f, 0, sizeof(f));
   f.x = y, f.w = ap->Wa, f.bias = ap->ba;
@@ -310,10 +311,20 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   int32_t rc = enqueue_fwd(f, st);
   if (rc) return rc;
   const HeadShape hs = head_shape(a, ad, B);
-  const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
+  const double u = (double)B * ad.Hu * ad.Wu * a->A;
   NF_RUN(st, "head_pool", 0.0, 4.0 * (u * (ks ? ks + 1.0 : 1.0) + (double)B * ad.F),
          launch_head_pool(hs, wsf(ws, w.U), wsf(ws, w.part), ks, ap->ba, wsf(ws, w.Pq),
                           reinterpret_cast<int32_t *>(wsf(ws, w.parg)), st));
+  return NF_OK;
+}
+
+// loss_out == nullptr: the batch mean is left to the backward launch that follows (run_bwd)
+int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const int32_t *labels,
+                    const nf_aux_params *ap, float *loss_out, void *ws, const WsLayout &w, hipStream_t st) {
+  int32_t rc = run_aux_features(a, ad, B, y, ap, ws, w, st);
+  if (rc) return rc;
+  const HeadShape hs = head_shape(a, ad, B);
+  const double fc = (double)a->n_classes * ad.F;
   NF_RUN(st, "head_fc", 4.0 * B * fc, 4.0 * (2.0 * B * fc + (double)B * (2.0 * ad.F + a->n_classes)),
          launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), wsf(ws, w.dPq), st));
   if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
@@ -555,6 +566,33 @@ int32_t nf_aux_fwd_loss(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B,
   const WsLayout w = ws_layout(d, ld, a, ad, B);
   if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
   return run_aux_fwd(a, ad, B, y, labels, ap, loss_out, ws, w, static_cast<hipStream_t>(stream));
+}
+
+int32_t nf_aux_predict(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *y,
+                       const int32_t *labels, const nf_aux_params *ap, int32_t *pred_out, int32_t *n_correct,
+                       int32_t accumulate, float *logits_out, void *ws, size_t ws_bytes, void *stream) {
+  LayerDims ld;
+  AuxDims ad;
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_aux(a, &ad))) return rc;
+  if ((rc = check_pair(d, ld, a))) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if (!y || !pred_out) return NF_ERR_NULL;
+  if ((labels == nullptr) != (n_correct == nullptr)) return NF_ERR_NULL;
+  if ((rc = check_aux_ptrs(ap))) return rc;
+  if (!aligned16(y)) return NF_ERR_BAD_DESC;
+  const WsLayout w = ws_layout(d, ld, a, ad, B);
+  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = run_aux_features(a, ad, B, y, ap, ws, w, st))) return rc;
+  const HeadShape hs = head_shape(a, ad, B);
+  const double fc = (double)a->n_classes * ad.F;
+  int32_t *hit = reinterpret_cast<int32_t *>(wsf(ws, w.loss_n));  // one flag per sample
+  NF_RUN(st, "head_predict", 2.0 * B * fc, 4.0 * (B * fc + (double)B * (ad.F + 2.0)),
+         launch_head_predict(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, logits_out, pred_out, hit, st));
+  if (labels) NF_RUN(st, "count_hits", 0.0, 4.0 * B, launch_count_hits(hit, B, n_correct, accumulate != 0, st));
+  return NF_OK;
 }
 
 int32_t nf_local_bwd_wgrad(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *x,

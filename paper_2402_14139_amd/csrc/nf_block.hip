@@ -29,12 +29,16 @@ struct BlockPlan {
 };
 
 // Shapes, chaining and shortcut wiring of the block, and its workspace plan at batch size B.
-// `train` selects whether the heads are part of the plan.
-int32_t plan_block(const nf_block *blk, int32_t B, int32_t B_last, bool train, BlockPlan *pl) {
+// mode: what the caller is going to run -- forward sweeps only, training passes (heads with
+// gradient buffers), or early-exit evaluation (heads without gradient buffers).
+enum PlanMode { PLAN_FWD = 0, PLAN_TRAIN = 1, PLAN_EVAL = 2 };
+int32_t plan_block(const nf_block *blk, int32_t B, int32_t B_last, PlanMode mode, BlockPlan *pl) {
   if (!blk) return NF_ERR_NULL;
   if (blk->n_layers <= 0 || blk->n_layers > 1024) return NF_ERR_BAD_DESC;
   if (!blk->layers || !blk->p) return NF_ERR_NULL;
-  if (train && (!blk->aux || !blk->ap || !blk->gp || !blk->ga)) return NF_ERR_NULL;
+  const bool train = mode == PLAN_TRAIN, heads = mode != PLAN_FWD;
+  if (heads && (!blk->aux || !blk->ap)) return NF_ERR_NULL;
+  if (train && (!blk->gp || !blk->ga)) return NF_ERR_NULL;
   if (B <= 0 || B > 65535 || B_last <= 0 || B_last > B) return NF_ERR_BAD_DESC;
   const int n = blk->n_layers;
   pl->y_off.assign(n, 0);
@@ -49,7 +53,7 @@ int32_t plan_block(const nf_block *blk, int32_t B, int32_t B_last, bool train, B
   }
   for (int l = 0; l < n; ++l) {
     const nf_layer_desc *d = &blk->layers[l];
-    const nf_aux_desc *a = train ? &blk->aux[l] : nullptr;
+    const nf_aux_desc *a = heads ? &blk->aux[l] : nullptr;
     int32_t Hp = 0, Wp = 0;
     int32_t rc = nf_layer_out_dims(d, nullptr, nullptr, &Hp, &Wp);
     if (rc) return rc;
@@ -73,12 +77,15 @@ int32_t plan_block(const nf_block *blk, int32_t B, int32_t B_last, bool train, B
     const nf_layer_params &p = blk->p[l];
     if (!p.W || !p.b || (d->skip_kind == 2 && !p.Wp)) return NF_ERR_NULL;
     if (!aligned16(p.W) || !aligned16(p.b) || (d->skip_kind == 2 && !aligned16(p.Wp))) return NF_ERR_BAD_DESC;
+    if (heads) {
+      const nf_aux_params &s = blk->ap[l];
+      if (!s.Wa || !s.ba || !s.Wf || !s.bf) return NF_ERR_NULL;
+    }
     if (train) {
       const nf_layer_params &g = blk->gp[l];
+      const nf_aux_params &s = blk->ga[l];
       if (!g.W || !g.b || (d->skip_kind == 2 && !g.Wp)) return NF_ERR_NULL;
-      const nf_aux_params *sets[2] = {&blk->ap[l], &blk->ga[l]};
-      for (const nf_aux_params *s : sets)
-        if (!s->Wa || !s->ba || !s->Wf || !s->bf) return NF_ERR_NULL;
+      if (!s.Wa || !s.ba || !s.Wf || !s.bf) return NF_ERR_NULL;
     }
     pl->y_elems[l] = (int64_t)d->C_out * Hp * Wp;
     pl->y_off[l] = off, off += up((size_t)B * pl->y_elems[l] * sizeof(float));
@@ -129,7 +136,8 @@ int32_t nf_block_workspace_bytes(const nf_block *blk, int32_t B, size_t *out) {
   if (!out) return NF_ERR_NULL;
   BlockPlan pl;
   // the heads are part of the plan whenever the block carries them
-  const int32_t rc = plan_block(blk, B, B, blk && blk->aux && blk->ap && blk->gp && blk->ga, &pl);
+  const PlanMode mode = (blk && blk->aux && blk->ap) ? ((blk->gp && blk->ga) ? PLAN_TRAIN : PLAN_EVAL) : PLAN_FWD;
+  const int32_t rc = plan_block(blk, B, B, mode, &pl);
   if (rc) return rc;
   *out = pl.total;
   return NF_OK;
@@ -145,7 +153,7 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
   const int64_t n_batches = (n_items + B - 1) / B;
   const int32_t B_last = (int32_t)(n_items - (n_batches - 1) * B);
   BlockPlan pl;
-  int32_t rc = plan_block(blk, B, B_last, true, &pl);
+  int32_t rc = plan_block(blk, B, B_last, PLAN_TRAIN, &pl);
   if (rc) return rc;
   if (s->momentum != 0.f) {
     if (!blk->vp || !blk->va) return NF_ERR_NULL;
@@ -216,7 +224,7 @@ int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, con
   const int64_t n_batches = (n_items + B - 1) / B;
   const int32_t B_last = (int32_t)(n_items - (n_batches - 1) * B);
   BlockPlan pl;
-  int32_t rc = plan_block(blk, B, B_last, false, &pl);
+  int32_t rc = plan_block(blk, B, B_last, PLAN_FWD, &pl);
   if (rc) return rc;
   if (!aligned16(cache_in) || !aligned16(cache_out)) return NF_ERR_BAD_DESC;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1)) || ws_bytes < pl.total) return NF_ERR_WORKSPACE;
@@ -236,6 +244,42 @@ int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, con
     }
     if ((rc = nf_cache_write(cache_out, labels_out, capacity_out, pl.se_out, j * B, nb, at(ws, pl.y_off[n - 1]), lab,
                              stream)))
+      return rc;
+  }
+  return NF_OK;
+}
+
+int32_t nf_block_evaluate(const nf_block *blk, int32_t exit_layer, int32_t B, int64_t n_items, const float *cache,
+                          const int32_t *cache_labels, int64_t capacity, int32_t *pred_out, int32_t *n_correct,
+                          void *ws, size_t ws_bytes, void *stream) {
+  if (!blk || !cache || !cache_labels || !pred_out || !n_correct) return NF_ERR_NULL;
+  if (n_items <= 0 || capacity <= 0 || B <= 0) return NF_ERR_BAD_DESC;
+  if (n_items > capacity) return NF_ERR_CACHE_RANGE;
+  if (exit_layer < 0 || exit_layer >= blk->n_layers) return NF_ERR_BAD_DESC;
+  const int64_t n_batches = (n_items + B - 1) / B;
+  const int32_t B_last = (int32_t)(n_items - (n_batches - 1) * B);
+  BlockPlan pl;
+  int32_t rc = plan_block(blk, B, B_last, PLAN_EVAL, &pl);
+  if (rc) return rc;
+  if (!aligned16(cache)) return NF_ERR_BAD_DESC;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1)) || ws_bytes < pl.total) return NF_ERR_WORKSPACE;
+  for (int64_t j = 0; j < n_batches; ++j) {
+    const int32_t nb = j == n_batches - 1 ? B_last : B;
+    int32_t *lab = reinterpret_cast<int32_t *>(at(ws, pl.lab_off[0]));
+    if ((rc = nf_cache_read(cache, cache_labels, capacity, pl.se_in, j * B, nullptr, nb, at(ws, pl.xin_off[0]), lab,
+                            stream)))
+      return rc;
+    for (int l = 0; l <= exit_layer; ++l) {
+      const nf_layer_desc *d = &blk->layers[l];
+      const float *xs = d->skip_kind ? input_of(pl, ws, blk->skip_src[l], 0) : nullptr;
+      if ((rc = nf_layer_fwd(d, nb, input_of(pl, ws, l, 0), xs, &blk->p[l], at(ws, pl.y_off[l]),
+                             at(ws, pl.layer_ws_off), pl.layer_ws_bytes, stream)))
+        return rc;
+    }
+    // the exit's head; the count of correct predictions accumulates over the batches
+    if ((rc = nf_aux_predict(&blk->layers[exit_layer], &blk->aux[exit_layer], nb, at(ws, pl.y_off[exit_layer]), lab,
+                             &blk->ap[exit_layer], pred_out + j * B, n_correct, j > 0, nullptr,
+                             at(ws, pl.layer_ws_off), pl.layer_ws_bytes, stream)))
       return rc;
   }
   return NF_OK;

@@ -114,6 +114,12 @@ hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int
 hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
                           const float *bf, float *dz, float *loss_n, float *dPq, hipStream_t st);
 hipError_t launch_loss_mean(const float *loss_n, int B, float *loss_out, hipStream_t st);
+// forward-only head: logits (optionally stored), predicted class per sample (largest logit, lowest
+// index among equal maxima) and, with labels, a 0/1 hit flag per sample
+hipError_t launch_head_predict(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
+                               const float *bf, float *logits_out, int32_t *pred, int32_t *hit, hipStream_t st);
+// *out = (accumulate ? *out : 0) + sum of the B hit flags
+hipError_t launch_count_hits(const int32_t *hit, int B, int32_t *out, bool accumulate, hipStream_t st);
 // one launch: dWf, dbf; dU (pool + aux ReLU backward); WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa
 // is given; the batch-mean loss when loss_out is given
 hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,

@@ -3,7 +3,9 @@
 // the exact number of device bytes one local step of a layer needs with this library (the caller
 // owns every buffer, so the figure is known without running anything), its linear models are
 // least-squares lines through that figure at the given batch sizes, and Algorithm 1 groups the
-// layers into blocks from those models.
+// layers into blocks from those models.  nf_select_exit is the choice of the output model
+// ("Trained Output CNN"): the early exit with the best validation accuracy and, among equals, the
+// fewest parameters.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -95,6 +97,16 @@ int32_t nf_partition(int32_t n_layers, const nf_linear_model *R, double M, int32
   }
   *n_blocks = nb;
   std::free(own);
+  return NF_OK;
+}
+
+int32_t nf_select_exit(int32_t n_exits, const int64_t *n_correct, const int64_t *n_params, int32_t *exit_out) {
+  if (!n_correct || !n_params || !exit_out) return NF_ERR_NULL;
+  if (n_exits <= 0) return NF_ERR_BAD_DESC;
+  int best = 0;
+  for (int e = 1; e < n_exits; ++e)
+    if (n_correct[e] > n_correct[best] || (n_correct[e] == n_correct[best] && n_params[e] < n_params[best])) best = e;
+  *exit_out = best;
   return NF_OK;
 }
 

@@ -244,3 +244,42 @@ def test_block_calls_validate_before_enqueue(L):
     nohead = nf.make_block(descs, None, skip, lp, None)
     assert train(nohead) == nf.NF_ERR_NULL
     assert L.nf_block_workspace_bytes(C.byref(nohead), B, C.byref(out)) == nf.NF_OK and out.value < need
+
+
+def test_evaluation_calls_validate_before_enqueue(L):
+    good = 0x10000
+    d, a = _layer(), _aux()
+    ap = nf.AuxParams(good, good, good, good)
+    need = nf.nf_workspace_bytes(d, a, 4)
+
+    def pred(y=good, lab=good, cnt=good, out=good, ws_bytes=need, a_=a):
+        return L.nf_aux_predict(C.byref(d), C.byref(a_), 4, y, lab, C.byref(ap), out, cnt, 0, None, good << 8, ws_bytes,
+                                None)
+
+    assert pred(y=None) == nf.NF_ERR_NULL
+    assert pred(out=None) == nf.NF_ERR_NULL
+    assert pred(lab=None) == nf.NF_ERR_NULL            # a counter without labels
+    assert pred(cnt=None) == nf.NF_ERR_NULL            # labels without a counter
+    assert pred(ws_bytes=need - 1) == nf.NF_ERR_WORKSPACE
+    assert pred(a_=_aux(head_pool=2)) == nf.NF_ERR_UNSUPPORTED
+    assert pred(a_=_aux(loss_kind=5)) == nf.NF_ERR_UNSUPPORTED
+    cfg, b, specs, blk = _cfg_block("cfg3", 1)
+    B = b.batch
+    bneed = nf.nf_block_workspace_bytes(blk, B)
+
+    def ev(e=0, n_items=2 * B, cap=4 * B, ws_bytes=bneed, pred_out=good, blk_=blk):
+        return L.nf_block_evaluate(C.byref(blk_), e, B, n_items, good, good, cap, pred_out, good, good << 8, ws_bytes,
+                                   None)
+
+    assert ev(e=-1) == nf.NF_ERR_BAD_DESC
+    assert ev(e=len(specs)) == nf.NF_ERR_BAD_DESC
+    assert ev(n_items=5 * B) == nf.NF_ERR_CACHE_RANGE
+    assert ev(pred_out=None) == nf.NF_ERR_NULL
+    assert ev(ws_bytes=bneed // 2) == nf.NF_ERR_WORKSPACE
+    out = C.c_int32()
+    one = (C.c_int64 * 1)(3)
+    assert L.nf_select_exit(0, one, one, C.byref(out)) == nf.NF_ERR_BAD_DESC
+    assert L.nf_select_exit(1, None, one, C.byref(out)) == nf.NF_ERR_NULL
+    assert nf.nf_select_exit([5, 9, 9, 7], [10, 30, 20, 40]) == 2
+    assert nf.nf_select_exit([5, 9, 9, 7], [10, 20, 30, 40]) == 1
+    assert nf.nf_select_exit([4, 4], [7, 7]) == 0

@@ -228,3 +228,98 @@ def test_block_epoch_is_the_sequence_of_local_steps_full_size(cfg_name, k):
     for mode, (l, s) in zip(("block", "block_prefetch"), results[1:]):
         assert torch.equal(l, base_l), mode
         assert len(s) == len(base_s) and all(torch.equal(a, b) for a, b in zip(s, base_s)), mode
+
+
+# ---- early-exit evaluation -----------------------------------------------------------------------
+def _check_predictions(tag, pred_gpu, logits_ref, pred_ref):
+    """Predictions are integers decided by fp32 logits: they must equal the oracle's wherever the
+    oracle's best logit leads the runner-up by more than rounding, and otherwise be one of the
+    classes within rounding of the best."""
+    z = np.asarray(logits_ref, np.float64)
+    top = z.max(axis=1)
+    tol = 2e-5 * np.abs(z).max()
+    near = z >= (top - tol)[:, None]
+    clear = near.sum(axis=1) == 1
+    assert np.array_equal(pred_gpu[clear], pred_ref[clear]), f"{tag}: prediction differs away from a tie"
+    assert np.all(near[np.arange(len(pred_gpu)), pred_gpu]), f"{tag}: predicted class is not a maximum"
+    return int((~clear).sum())
+
+
+@pytest.mark.parametrize("case", ["a8", "a5_scalar", "a80_wide", "a4_split"])
+def test_aux_predict_matches_oracle(case):
+    L = workloads.LayerSpec
+    spec, B, cls = {"a8": (L("t", 8, 12, 12, 24, A=8), 37, 10),
+                    "a5_scalar": (L("t", 3, 10, 10, 6, A=5), 5, 7),
+                    "a80_wide": (L("t", 32, 8, 8, 160, A=80), 6, 200),
+                    "a4_split": (L("t", 16, 6, 6, 256, A=4), 5, 10)}[case]
+    x, _, labels, p = G.make_inputs(spec, B, cls, seed=31)
+    (d, a), (od, oa) = G.descs(spec, cls)
+    gl = G.gpu_layer(spec, cls, p, B, False)
+    y = gl.forward(G.to_dev(layout.act_to_lib(x)))
+    pred = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), 1000, dtype=torch.int32, device="cuda")
+    logits = torch.empty((B, cls), device="cuda")
+    nf.nf_aux_predict(gl.d, gl.a, B, y, G.to_dev(labels), gl.sa, pred, cnt, False, logits, gl.ws)
+    nf.nf_aux_predict(gl.d, gl.a, B, y, G.to_dev(labels), gl.sa, pred, cnt, True, None, gl.ws)   # accumulates
+    torch.cuda.synchronize()
+    oy = O.layer_fwd(od, x, None, p["W"], p["b"]).Y
+    z, opred = O.aux_predict(oa, oy, p["Wa"], p["ba"], p["Wf"], p["bf"])
+    G.assert_close("logits", logits.cpu().numpy(), z)
+    pg = pred.cpu().numpy()
+    _check_predictions(case, pg, z, opred)
+    assert int(cnt.item()) == 2 * int((pg == labels).sum())
+    # without labels nothing is counted
+    nf.nf_aux_predict(gl.d, gl.a, B, y, None, gl.sa, pred, None, False, None, gl.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(pred.cpu().numpy(), pg)
+
+
+def test_aux_predict_ties_go_to_the_lowest_class():
+    spec, B, cls = workloads.LayerSpec("t", 8, 6, 6, 16, A=8), 4, 300
+    x, _, labels, p = G.make_inputs(spec, B, cls, seed=32)
+    p["Wf"][:] = 0
+    p["bf"][:] = -1.0
+    p["bf"][[257, 40, 299]] = 2.5                 # three equal maxima, the lowest in another thread's stride
+    gl = G.gpu_layer(spec, cls, p, B, False)
+    y = gl.forward(G.to_dev(layout.act_to_lib(x)))
+    pred = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    lab = np.array([40, 257, 40, 0], np.int32)
+    nf.nf_aux_predict(gl.d, gl.a, B, y, G.to_dev(lab), gl.sa, pred, cnt, False, None, gl.ws)
+    torch.cuda.synchronize()
+    assert pred.cpu().tolist() == [40] * B and int(cnt.item()) == 2
+
+
+@pytest.mark.parametrize("kind", ["pool_basic", "proj"])
+def test_block_evaluate_matches_oracle(kind):
+    specs, skip = _small_block(kind)
+    cls, N, B = 10, 23, 6
+    X, lab, _, params = _gen(specs, cls, N, seed=23)
+    gb = GpuBlock(specs, skip, cls, params, B, False)
+    cache = G.to_dev(layout.act_to_lib(X).reshape(N, -1))
+    clab = G.to_dev(lab)
+    obl = [O.BlockLayer(O.layer_desc(**ls.layer_desc_fields()), O.aux_desc(**ls.aux_desc_fields(cls)), p, None, s)
+           for ls, p, s in zip(specs, params, skip)]
+    counts, ocounts = [], []
+    for e in range(len(specs)):
+        pred = torch.full((N + 2,), -7, dtype=torch.int32, device="cuda")
+        cnt = torch.full((1,), 999, dtype=torch.int32, device="cuda")
+        nf.nf_block_evaluate(gb.blk, e, B, N, cache, clab, N, pred, cnt, gb.ws)
+        torch.cuda.synchronize()
+        pg = pred.cpu().numpy()
+        assert np.all(pg[N:] == -7)
+        opred, ocorrect = O.block_evaluate(obl, e, X.reshape(N, -1), lab, N, B, X.shape[1:])
+        # the oracle's logits for the margin test
+        inputs = [X]
+        for n in range(e + 1):
+            xs = None if skip[n] < 0 else inputs[skip[n]]
+            inputs.append(O.layer_fwd(obl[n].d, inputs[n], xs, params[n]["W"], params[n]["b"], params[n].get("Wp")).Y)
+        z, _ = O.aux_predict(obl[e].a, inputs[-1], params[e]["Wa"], params[e]["ba"], params[e]["Wf"], params[e]["bf"])
+        ties = _check_predictions(f"{kind} exit {e}", pg[:N], z, opred)
+        assert int(cnt.item()) == int((pg[:N] == lab).sum())
+        if ties == 0:
+            assert int(cnt.item()) == ocorrect
+        counts.append(int(cnt.item()))
+        ocounts.append(ocorrect)
+    n_params = np.cumsum([sum(v.size for k, v in p.items() if v is not None and k in ("W", "b", "Wp")) for p in params])
+    assert nf.nf_select_exit(counts, [int(v) for v in n_params]) == O.select_exit(counts, [int(v) for v in n_params])
