@@ -282,7 +282,10 @@ def main():
     if not args.no_prof:
         main_s, side_s = torch.cuda.Stream(), torch.cuda.Stream()
         tot = {"plain": 0.0, "prefetch": 0.0}
-        fill_ms, fill_bytes = 0.0, 0.0
+        fill_ms, eval_ms = 0.0, 0.0
+        n_eval = min(N, 2048)
+        epred = torch.empty((n_eval,), dtype=torch.int32, device=dev)
+        ecnt = torch.zeros((1,), dtype=torch.int32, device=dev)
         for k, b in enumerate(cfg.blocks):
             Ls = [layers[li] for li in b.layers]
             skip = [(-1 if not cfg.layers[li].skip_kind else cfg.layers[li].skip_src - b.layers[0]) for li in b.layers]
@@ -306,14 +309,24 @@ def main():
                                        bws, stream=main_s)
                 main_s.synchronize()
                 fill_ms += (time.perf_counter() - t0) * 1e3
+            # early-exit evaluation at the block's last layer over n_eval samples of its input cache
+            t0 = time.perf_counter()
+            nf.nf_block_evaluate(blk, len(Ls) - 1, b.batch, n_eval, caches[k], clabels[k], N, epred, ecnt, bws,
+                                 stream=main_s)
+            main_s.synchronize()
+            eval_ms += (time.perf_counter() - t0) * 1e3
             del bws
         block_driver = {"ms_per_step": round(tot["plain"], 4), "ms_per_step_prefetch": round(tot["prefetch"], 4),
                         "note": "nf_block_train_epoch per block (no cache write inside a training pass), summed "
                                 "over blocks per batch; prefetch = cache read of the next batch on a second stream",
                         "fill_cache_sweep_ms": round(fill_ms, 2),
-                        "fill_cache_images_per_s": round((nblk - 1) * N / (fill_ms * 1e-3), 1) if fill_ms else None}
+                        "fill_cache_images_per_s": round((nblk - 1) * N / (fill_ms * 1e-3), 1) if fill_ms else None,
+                        "evaluate_images_per_s": round(nblk * n_eval / (eval_ms * 1e-3), 1),
+                        "evaluate_note": f"nf_block_evaluate at each block's last exit over {n_eval} samples of "
+                                         "its input cache (forward of the block + that exit's head + arg-max)"}
         log(f"[block] train pass {tot['plain']:.3f} ms/step, with prefetch {tot['prefetch']:.3f} ms/step; "
-            f"cache-fill sweeps of {nblk - 1} blocks x {N} samples {fill_ms:.1f} ms")
+            f"cache-fill sweeps of {nblk - 1} blocks x {N} samples {fill_ms:.1f} ms; evaluation of {nblk} exits x "
+            f"{n_eval} samples {eval_ms:.1f} ms")
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     cpu = None
