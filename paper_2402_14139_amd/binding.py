@@ -86,6 +86,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2402_14139_amd.build` "
                                "(or __graft_entry__.build()); there is no fallback path")
+        # PyTorch ships its own copy of the HIP runtime; it must be in the process before libnf.so
+        # is loaded, so that both use the same runtime (with two runtimes the second one finds no
+        # device and every launch of libnf fails)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.nf_strerror.restype = C.c_char_p
         L.nf_strerror.argtypes = [C.c_int32]

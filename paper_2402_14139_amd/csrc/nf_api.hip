@@ -3,6 +3,7 @@
 // NeuroFlux, arXiv 2402.14139).  No device work is enqueued before validation has passed.
 #include <algorithm>
 #include <cstdint>
+#include <cstdio>
 #include <cstring>
 #include <vector>
 
@@ -167,9 +168,15 @@ int32_t check_ws(const void *ws, size_t have, size_t need) {
 
 inline float *wsf(void *ws, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(ws) + off); }
 
-#define NF_HIP(expr)                       \
-  do {                                     \
-    if ((expr) != hipSuccess) return NF_ERR_DEVICE; \
+// A HIP error while enqueueing is reported on stderr with the failing expression (the status code
+// alone cannot say which launch it was), then returned as NF_ERR_DEVICE.
+#define NF_HIP(expr)                                                                     \
+  do {                                                                                   \
+    const hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) {                                                              \
+      std::fprintf(stderr, "libnf: %s: %s\n", hipGetErrorString(e_), #expr);             \
+      return NF_ERR_DEVICE;                                                              \
+    }                                                                                    \
   } while (0)
 
 // ---- optional kernel timing (nf_prof_begin / nf_prof_end): one HIP-event pair per launch ----

@@ -24,7 +24,7 @@ def make_descs(spec, n_classes):
 
 class LocalLayer:
     def __init__(self, d: nf.LayerDesc, a: nf.AuxDesc, params_lib: dict, max_batch: int, momentum: bool,
-                 device="cuda"):
+                 device="cuda", own_workspace: bool = True):
         if not torch.cuda.is_available():
             raise RuntimeError("LocalLayer needs a GPU: the library has no CPU path")
         nf.lib()
@@ -35,8 +35,9 @@ class LocalLayer:
                   for k in PARAM_NAMES}
         self.g = {k: (None if v is None else torch.zeros_like(v)) for k, v in self.p.items()}
         self.v = {k: (None if v is None else torch.zeros_like(v)) for k, v in self.p.items()} if momentum else None
-        self.ws_bytes = nf.nf_workspace_bytes(d, a, max_batch)
-        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        # layers driven through the block-level calls share the block's workspace instead
+        self.ws_bytes = nf.nf_workspace_bytes(d, a, max_batch) if own_workspace else 0
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device) if own_workspace else None
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         self._structs()
 

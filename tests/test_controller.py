@@ -1,0 +1,75 @@
+"""The Controller loop (partition -> train blocks one after the other -> fill caches -> evaluate
+every exit -> select the output model).  The planning part is host-only; the run needs the GPU."""
+import numpy as np
+import pytest
+
+import workloads
+from paper_2402_14139_amd import controller as CT
+
+
+def _net():
+    """Small ResNet-style network on 16x16 inputs: stem, one basic block per stage, three stages."""
+    layers = workloads.resnet_layers([1, 1, 1], widths=(16, 32, 64), in_shape=(3, 16, 16))
+    for l in layers:
+        l.A = 8
+    return layers
+
+
+def test_plan_blocks_on_host():
+    specs = _net()
+    b, plans = CT.plan_blocks(specs, 4, True, 4 << 20, 128)
+    assert len(b) == len(specs) and all(0 < v <= 128 for v in b) and len(plans) >= 2
+    # contiguous cover, every shortcut source inside its block, block batch = min over its layers
+    assert plans[0].first == 0 and plans[-1].last == len(specs) - 1
+    for p, q in zip(plans[:-1], plans[1:]):
+        assert q.first == p.last + 1
+    for p in plans:
+        assert p.batch == min(b[p.first:p.last + 1])
+        for l in range(p.first, p.last + 1):
+            assert not specs[l].skip_kind or specs[l].skip_src >= p.first
+    # a generous budget: one block at the limit
+    b2, plans2 = CT.plan_blocks(specs, 4, True, 8 << 30, 128)
+    assert b2 == [128] * len(specs) and len(plans2) == 1 and plans2[0].batch == 128
+    with pytest.raises(ValueError):
+        CT.plan_blocks(specs, 4, True, 1 << 10, 128)
+
+
+def test_respect_shortcuts_merges_cut_basic_blocks():
+    specs = _net()   # layers: stem, s1c1, s1c2(skip 1), s2c1, s2c2(skip 3), s3c1, s3c2(skip 5)
+    P = CT.BlockPlan
+    got = CT.respect_shortcuts([P(0, 1, 32), P(2, 3, 64), P(4, 6, 128)], specs)
+    assert [(p.first, p.last, p.batch) for p in got] == [(0, 6, 32)]
+    got = CT.respect_shortcuts([P(0, 2, 32), P(3, 4, 64), P(5, 6, 128)], specs)
+    assert [(p.first, p.last, p.batch) for p in got] == [(0, 2, 32), (3, 4, 64), (5, 6, 128)]
+    got = CT.respect_shortcuts([P(0, 2, 32), P(3, 5, 64), P(6, 6, 128)], specs)
+    assert [(p.first, p.last, p.batch) for p in got] == [(0, 2, 32), (3, 6, 64)]
+
+
+@pytest.mark.gpu
+def test_pipeline_learns_a_separable_task():
+    """Whole method on a learnable synthetic task (class pattern + noise, 4 classes): blocks from
+    Algorithm 1 under a small budget, two passes per block, caches in between, every exit
+    evaluated on held-out samples.  Chance is 25 %; the selected exit must be far above it, the
+    losses must fall, and the exits' parameter counts must grow with depth."""
+    import torch
+    from paper_2402_14139_amd import layout
+    specs = _net()
+    cls, N, NV = 4, 1024, 512
+    b, plans = CT.plan_blocks(specs, cls, True, 4 << 20, 128)
+    assert len(plans) >= 2, plans
+    params = [workloads.gen_layer_params(77, i, ls, cls) for i, ls in enumerate(specs)]
+    x, y = workloads.gen_class_patterns(5, N + NV, (3, 16, 16), cls)
+    rows = torch.from_numpy(layout.act_to_lib(x).reshape(N + NV, -1)).cuda()
+    labels = torch.from_numpy(y).cuda()
+    tr = CT.Trainer(specs, cls, params, plans, momentum=True)
+    losses = tr.train(rows[:N].contiguous(), labels[:N].contiguous(), epochs=2, lr=0.01, mu=0.9, seed=3)
+    torch.cuda.synchronize()
+    for lk in losses:
+        l = lk.cpu().numpy()
+        assert np.isfinite(l).all()
+        assert l[-1, -4:].mean() < 0.5 * l[0, :4].mean(), (l[0, :4], l[-1, -4:])
+    correct, n_params = tr.evaluate_exits(rows[N:].contiguous(), labels[N:].contiguous())
+    assert len(correct) == len(specs) and n_params == sorted(n_params) and len(set(n_params)) == len(specs)
+    e = tr.select_exit(correct, n_params)
+    print("plans", plans, "correct", correct, "exit", e, flush=True)
+    assert correct[e] == max(correct) and correct[e] >= 0.9 * NV

@@ -10,4 +10,4 @@ OIHW convolution weights, [out][in] linear weights, int32 labels.
 """
 from .configs import (Block, Config, LayerSpec, config, config_names, resnet_layers,  # noqa: F401
                       vgg_layers)
-from .gen import gen_batch, gen_layer_params, rng_for  # noqa: F401
+from .gen import gen_batch, gen_class_patterns, gen_layer_params, rng_for  # noqa: F401

@@ -52,3 +52,13 @@ def gen_layer_params(seed: int, layer_index: int, spec, n_classes: int, dtype=np
     p["Wf"] = _kaiming(g, (n_classes, F), F, dtype)
     p["bf"] = bias(n_classes)
     return p
+
+
+def gen_class_patterns(seed: int, N: int, shape, n_classes: int, noise: float = 0.7, dtype=np.float32):
+    """A learnable stand-in data set: every class has a fixed N(0,1) pattern; a sample is its
+    class's pattern plus ``noise`` * N(0,1).  Returns (x [N,C,H,W], labels [N] int32)."""
+    g = rng_for(seed, "class-patterns", n_classes)
+    patterns = g.standard_normal((n_classes,) + tuple(shape))
+    y = g.integers(0, n_classes, size=(N,), dtype=np.int64).astype(np.int32)
+    x = patterns[y] + noise * g.standard_normal((N,) + tuple(shape))
+    return x.astype(dtype), y
