@@ -59,3 +59,14 @@ def test_wide_heads_full_batch(cfg_name, li):
     convolution, its weight gradient and its data gradient are then full-width MFMA GEMMs."""
     cfg = workloads.config(cfg_name)
     _run(cfg_name, li, cfg.blocks[cfg.layers[li].block].batch)
+
+
+@pytest.mark.parametrize("cfg_name,li", [("cfg4", 0), ("cfg4", 1), ("cfg4", 3), ("cfg4", 6), ("cfg4", 8), ("cfg4", 12),
+                                         ("cfg5", 0), ("cfg5", 1), ("cfg5", 7), ("cfg5", 8), ("cfg5", 15),
+                                         ("cfg5", 16), ("cfg5", 21), ("cfg5", 27), ("cfg5", 28)])
+def test_cfg4_cfg5_sampled_layers_full_batch(cfg_name, li):
+    """The VGG-16- and ResNet-34-style configurations at their own block batch sizes (32 ... 512):
+    64x64 and 128x128 inputs, the 7x7 stride-2 stem with its 3x3/s2/p1 max-pool, pooled VGG layers,
+    stride-2 and projection-shortcut layers, the 512-sample stage-3 layers."""
+    cfg = workloads.config(cfg_name)
+    _run(cfg_name, li, cfg.blocks[cfg.layers[li].block].batch)
