@@ -281,7 +281,7 @@ def main():
     block_driver = None
     if not args.no_prof:
         main_s, side_s = torch.cuda.Stream(), torch.cuda.Stream()
-        tot = {"plain": 0.0, "prefetch": 0.0}
+        tot = {"plain": 0.0, "prefetch": 0.0, "graph": 0.0}
         fill_ms, eval_ms = 0.0, 0.0
         n_eval = min(N, 2048)
         epred = torch.empty((n_eval,), dtype=torch.int32, device=dev)
@@ -303,6 +303,18 @@ def main():
                                         perms[k], bl, bws, stream=main_s, prefetch_stream=pf)
                 main_s.synchronize()
                 tot[mode] += (time.perf_counter() - t0) * 1e3 / nb / 2
+            # the same pass captured once in a HIP graph and replayed
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                nf.nf_block_train_epoch(blk, cfg.lr, cfg.momentum, b.batch, nb * b.batch, caches[k], clabels[k], N,
+                                        perms[k], bl, bws)
+            torch.cuda.synchronize()
+            for _ in range(2):
+                t0 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                tot["graph"] += (time.perf_counter() - t0) * 1e3 / nb / 2
+            del graph
             if k + 1 < nblk:
                 t0 = time.perf_counter()
                 nf.nf_block_fill_cache(blk, b.batch, N, caches[k], clabels[k], N, wcaches[k + 1], wlabels[k + 1], N,
@@ -317,6 +329,7 @@ def main():
             eval_ms += (time.perf_counter() - t0) * 1e3
             del bws
         block_driver = {"ms_per_step": round(tot["plain"], 4), "ms_per_step_prefetch": round(tot["prefetch"], 4),
+                        "ms_per_step_hip_graph": round(tot["graph"], 4),
                         "note": "nf_block_train_epoch per block (no cache write inside a training pass), summed "
                                 "over blocks per batch; prefetch = cache read of the next batch on a second stream",
                         "fill_cache_sweep_ms": round(fill_ms, 2),
@@ -324,7 +337,8 @@ def main():
                         "evaluate_images_per_s": round(nblk * n_eval / (eval_ms * 1e-3), 1),
                         "evaluate_note": f"nf_block_evaluate at each block's last exit over {n_eval} samples of "
                                          "its input cache (forward of the block + that exit's head + arg-max)"}
-        log(f"[block] train pass {tot['plain']:.3f} ms/step, with prefetch {tot['prefetch']:.3f} ms/step; "
+        log(f"[block] train pass {tot['plain']:.3f} ms/step, with prefetch {tot['prefetch']:.3f} ms/step, "
+            f"replayed from a HIP graph {tot['graph']:.3f} ms/step; "
             f"cache-fill sweeps of {nblk - 1} blocks x {N} samples {fill_ms:.1f} ms; evaluation of {nblk} exits x "
             f"{n_eval} samples {eval_ms:.1f} ms")
 

@@ -323,3 +323,37 @@ def test_block_evaluate_matches_oracle(kind):
         ocounts.append(ocorrect)
     n_params = np.cumsum([sum(v.size for k, v in p.items() if v is not None and k in ("W", "b", "Wp")) for p in params])
     assert nf.nf_select_exit(counts, [int(v) for v in n_params]) == O.select_exit(counts, [int(v) for v in n_params])
+
+
+def test_block_epoch_under_graph_capture():
+    """The block pass allocates nothing and records no memset, so a caller can capture it in a HIP
+    graph: three replays (with eager work and synchronisations in between) leave bit-for-bit the
+    state that three eager calls leave, checked after every replay."""
+    specs, skip = _small_block("proj")
+    cls, N, B, lr, mu = 10, 12, 6, 0.02, 0.9
+    X, lab, idx, params = _gen(specs, cls, N, seed=24)
+    cache = G.to_dev(layout.act_to_lib(X).reshape(N, -1))
+    clab, didx = G.to_dev(lab), G.to_dev(idx)
+    nb = N // B
+    eager = GpuBlock(specs, skip, cls, params, B, True)
+    el = torch.zeros((nb, len(specs)), device="cuda")
+    eager_states = []
+    for _ in range(3):
+        nf.nf_block_train_epoch(eager.blk, lr, mu, B, N, cache, clab, N, didx, el, eager.ws)
+        torch.cuda.synchronize()
+        eager_states.append(([s.clone() for s in eager.state()], el.clone()))
+    cap = GpuBlock(specs, skip, cls, params, B, True)
+    gl = torch.zeros((nb, len(specs)), device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        nf.nf_block_train_epoch(cap.blk, lr, mu, B, N, cache, clab, N, didx, gl, cap.ws)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for r in range(3):
+        graph.replay()
+        scratch.add_(1.0).sum().item()          # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        want_state, want_loss = eager_states[r]
+        assert torch.equal(gl, want_loss), f"losses differ after replay {r}"
+        assert all(torch.equal(a, b) for a, b in zip(cap.state(), want_state)), f"state differs after replay {r}"
