@@ -274,6 +274,34 @@ def main():
         log(f"[layer] {li:2d} {ls.name:<8} blk{ls.block} B={B:<4d} {ms:8.3f} ms {B / (ms * 1e-3):10.0f} img/s "
             f"{fl / (ms * 1e-3) / 1e12:7.2f} TFLOP/s")
 
+    per_block = []
+    for k, b in enumerate(cfg.blocks):
+        ms = sum(per_layer[li]["ms"] for li in b.layers)
+        per_block.append({"block": k, "B": b.batch, "layers": len(b.layers), "ms": round(ms, 4),
+                          "images_per_s": round(b.batch / (ms * 1e-3), 1)})
+
+    # ---- the device's own figures: fp32 MFMA peak from CU count x clock (64 flop/clk/SIMD, 4 SIMDs
+    # per CU), and a measured plain-copy bandwidth (1 GiB read + 1 GiB written) as the practical
+    # HBM ceiling next to the published 8 TB/s
+    prop = torch.cuda.get_device_properties(0)
+    cus, clock_khz = nf.nf_device_info()
+    device = {"name": prop.name, "compute_units": cus, "clock_mhz": round(clock_khz / 1e3, 1),
+              "mfma_f32_peak_tflops_from_props": round(cus * 256 * clock_khz * 1e3 / 1e12, 1)}
+    if not args.no_prof:
+        rows, se_c = 4096, 65536
+        src = torch.ones((rows, se_c), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        nf.nf_cache_read(src, None, rows, se_c, 0, None, rows, dst, None)
+        e0.record()
+        for _ in range(5):
+            nf.nf_cache_read(src, None, rows, se_c, 0, None, rows, dst, None)
+        e1.record()
+        torch.cuda.synchronize()
+        device["copy_1gib_gbs"] = round(5 * 2 * rows * se_c * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del src, dst
+    log(f"[device] {device}")
+
     # ---- the same work through the block-level calls (Worker loop inside the library) ----------
     # per block: nf_block_train_epoch over `steps` shuffled batches of its cache, without and with
     # the prefetch stream (read of batch j+1 overlapping the training of batch j); then the
@@ -402,7 +430,7 @@ def main():
         "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
         "losses_finite": finite,
         "roofline": roofline, "cpu_baseline": cpu, "block_driver": block_driver, "kernels": kernels,
-        "layers": per_layer,
+        "layers": per_layer, "blocks": per_block, "device": device,
     }
     print(json.dumps(out), flush=True)
 

@@ -272,6 +272,9 @@ typedef struct {
   int64_t launches;
   double ms, flops, bytes;
 } nf_prof_record;
+/* Compute units and peak shader clock (kHz) of the current device, as the runtime reports them
+ * (the fp32 MFMA peak is compute_units x 4 SIMDs x 64 flop/clk x clock). */
+int32_t nf_device_info(int32_t *compute_units, int32_t *clock_khz);
 int32_t nf_prof_begin(void);
 int32_t nf_prof_end(nf_prof_record *out, int32_t cap, int32_t *n);
 

@@ -21,7 +21,8 @@ EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_f
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
            "nf_block_train_epoch", "nf_block_fill_cache", "nf_layer_step_bytes", "nf_fit_linear",
-           "nf_profile_layer", "nf_partition", "nf_aux_predict", "nf_block_evaluate", "nf_select_exit")
+           "nf_profile_layer", "nf_partition", "nf_aux_predict", "nf_block_evaluate", "nf_select_exit",
+           "nf_device_info")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
 NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
@@ -131,6 +132,7 @@ def lib():
         L.nf_block_evaluate.argtypes = [C.POINTER(Block), C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nf_select_exit.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.nf_device_info.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.nf_layer_step_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
                                           C.POINTER(C.c_size_t)]
         L.nf_fit_linear.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(LinearModel)]
@@ -366,3 +368,10 @@ def nf_select_exit(n_correct, n_params) -> int:
     _check(lib().nf_select_exit(n, (C.c_int64 * n)(*n_correct), (C.c_int64 * n)(*n_params), C.byref(out)),
            "nf_select_exit")
     return int(out.value)
+
+
+def nf_device_info():
+    """(compute units, peak shader clock in kHz) of the current device."""
+    cu, khz = C.c_int32(), C.c_int32()
+    _check(lib().nf_device_info(C.byref(cu), C.byref(khz)), "nf_device_info")
+    return int(cu.value), int(khz.value)

@@ -707,6 +707,16 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
   return run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, loss_out, s, vp, va, ws, w, st);
 }
 
+int32_t nf_device_info(int32_t *compute_units, int32_t *clock_khz) {
+  if (!compute_units || !clock_khz) return NF_ERR_NULL;
+  int dev = 0, cu = 0, khz = 0;
+  NF_HIP(hipGetDevice(&dev));
+  NF_HIP(hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev));
+  NF_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev));
+  *compute_units = cu, *clock_khz = khz;
+  return NF_OK;
+}
+
 int32_t nf_prof_begin(void) {
   for (auto &e : g_prof.ev) {
     (void)hipEventDestroy(e.a);
