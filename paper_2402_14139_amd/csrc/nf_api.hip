@@ -435,10 +435,10 @@ int32_t enqueue_sgd(const SgdTensors &t, hipStream_t st) {
   return NF_OK;
 }
 
-int32_t enqueue_cache_copy(const float *src, float *dst, const int32_t *sl, int32_t *dl, long long se,
-                           long long sfirst, long long dfirst, const long long *idx, long long cap, int B,
-                           hipStream_t st) {
-  NF_RUN(st, "cache_copy", 0.0, 8.0 * (double)se * B + (sl ? 8.0 * B : 0.0) + (idx ? 8.0 * B : 0.0),
+int32_t enqueue_cache_copy(const char *name, const float *src, float *dst, const int32_t *sl, int32_t *dl,
+                           long long se, long long sfirst, long long dfirst, const long long *idx, long long cap,
+                           int B, hipStream_t st) {
+  NF_RUN(st, name, 0.0, 8.0 * (double)se * B + (sl ? 8.0 * B : 0.0) + (idx ? 8.0 * B : 0.0),
          launch_cache_copy(src, dst, sl, dl, se, sfirst, dfirst, idx, cap, B, st));
   return NF_OK;
 }
@@ -657,7 +657,7 @@ int32_t nf_cache_write(float *cache, int32_t *cache_labels, int64_t capacity, in
                        int64_t first, int32_t B, const float *y, const int32_t *labels, void *stream) {
   const int32_t rc = check_cache(cache, cache_labels, capacity, sample_elems, first, B, y, labels);
   if (rc) return rc;
-  return enqueue_cache_copy(y, cache, labels, cache_labels, sample_elems, 0, first, nullptr, capacity, B,
+  return enqueue_cache_copy("cache_write", y, cache, labels, cache_labels, sample_elems, 0, first, nullptr, capacity, B,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -668,7 +668,7 @@ int32_t nf_cache_read(const float *cache, const int32_t *cache_labels, int64_t c
                                  labels_out);
   if (rc) return rc;
   if (B <= 0 || B > 65535) return NF_ERR_BAD_DESC;
-  return enqueue_cache_copy(cache, x_out, cache_labels, labels_out, sample_elems, first, 0,
+  return enqueue_cache_copy("cache_read", cache, x_out, cache_labels, labels_out, sample_elems, first, 0,
                             reinterpret_cast<const long long *>(idx), capacity, B, static_cast<hipStream_t>(stream));
 }
 
