@@ -288,17 +288,18 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(ReduceSgd r) {
     if (ji >= r.njobs) break;
     const WgradReduce &jb = r.job[ji];
     if (b < jb.main_blocks && jb.direct) {
-      // few splits, 16-byte aligned tensors: one thread per group of four, every load issued
-      // before the first add, no LDS
+      // up to eight splits, 16-byte aligned tensors: one thread per group of four, every load
+      // (partials, weight, momentum) issued before the first add, no LDS; partials are added in
+      // split order
       const long long n4 = ((long long)jb.P * jb.Qld) >> 2;
       const long long i4 = (long long)b * 256 + t;
       if (i4 >= n4) return;
       const float4 *src = reinterpret_cast<const float4 *>(jb.part) + i4;
       const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-      const float4 a0 = src[0];
-      const float4 a1 = jb.splits > 1 ? src[n4] : zero;
-      const float4 a2 = jb.splits > 2 ? src[2 * n4] : zero;
-      const float4 a3 = jb.splits > 3 ? src[3 * n4] : zero;
+      constexpr int DMAX = 8;  // the launcher takes this path for at most DMAX splits
+      float4 a[DMAX];
+#pragma unroll
+      for (int z = 0; z < DMAX; ++z) a[z] = z < jb.splits ? src[(long long)z * n4] : zero;
       const long long e = i4 << 2;
       const int pr = (int)(e / jb.Qld), q = (int)(e - (long long)pr * jb.Qld);
       const bool first = q < jb.Q0;
@@ -307,10 +308,10 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(ReduceSgd r) {
       const bool mom = v && r.mu != 0.f;
       const float4 vv = (w && mom) ? *reinterpret_cast<const float4 *>(v + o) : zero;
       float4 wv = w ? *reinterpret_cast<const float4 *>(w + o) : zero;
-      float4 g = a0;
-      if (jb.splits > 1) g.x += a1.x, g.y += a1.y, g.z += a1.z, g.w += a1.w;
-      if (jb.splits > 2) g.x += a2.x, g.y += a2.y, g.z += a2.z, g.w += a2.w;
-      if (jb.splits > 3) g.x += a3.x, g.y += a3.y, g.z += a3.z, g.w += a3.w;
+      float4 g = a[0];
+#pragma unroll
+      for (int z = 1; z < DMAX; ++z)
+        if (z < jb.splits) g.x += a[z].x, g.y += a[z].y, g.z += a[z].z, g.w += a[z].w;
       *reinterpret_cast<float4 *>(out + o) = g;
       if (w) {
         if (mom) {
@@ -489,7 +490,7 @@ hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r0, hipStream_t st) {
                al16(jb.w1) && al16(jb.v0) && al16(jb.v1))
                   ? 1
                   : 0;
-    jb.direct = (jb.vec4 && jb.splits <= 4) ? 1 : 0;
+    jb.direct = (jb.vec4 && jb.splits <= 8) ? 1 : 0;
     jb.main_blocks = jb.direct ? (int)((n4 + 255) / 256) : (int)((n4 + cols - 1) / cols);
     jb.bias_blocks = jb.ob ? (jb.P + 15) / 16 : 0;
     blocks += (unsigned)(jb.main_blocks + jb.bias_blocks);
