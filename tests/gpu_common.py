@@ -10,6 +10,7 @@ from paper_2402_14139_amd import layout
 from paper_2402_14139_amd.layer import PARAM_NAMES, LocalLayer
 
 REL = 1e-4  # tolerance of the build target: 1e-4 relative on losses, gradients, updated weights
+LOSS_FLOOR = 1e-6  # absolute floor for a loss that has reached zero to within fp32 rounding of the logits
 
 
 def assert_close(name, got, ref, rel=REL):
@@ -177,7 +178,9 @@ def run_step_both(spec, n_classes, B, seed, lr, mu, steps=1, relu=1, bias_std=0.
 
 def check_step_results(tag, out, final):
     for si, ((gl, gg, gy), (ol, og, oy)) in enumerate(out):
-        assert abs(gl - ol) <= REL * abs(ol), f"{tag} step {si}: loss {gl} vs {ol}"
+        # the loss is a difference of logit-sized numbers (log-sum-exp minus the label's logit): when
+        # a batch is fitted to ~0 its fp32 value bottoms out at the rounding of those, hence the floor
+        assert abs(gl - ol) <= REL * abs(ol) + LOSS_FLOOR, f"{tag} step {si}: loss {gl} vs {ol}"
         assert_close(f"{tag} step {si} y", gy, oy)
         for k in PARAM_NAMES:
             if og[k] is not None:

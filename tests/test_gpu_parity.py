@@ -272,3 +272,41 @@ def test_run_to_run_determinism(name):
         res.append(out)
     for k in res[0]:
         assert torch.equal(res[0][k], res[1][k]), k
+
+
+def _random_case(seed):
+    """A seeded random local layer: channel counts with and without the multiples of 4 the vector
+    paths need, odd map sizes, every filter size / stride / pooling / shortcut the library accepts."""
+    g = np.random.default_rng(1000 + seed)
+    C = int(g.choice([3, 4, 6, 8, 12, 16, 20, 32]))
+    K = int(g.choice([4, 6, 8, 12, 16, 24, 40, 64, 72]))
+    A = int(g.choice([1, 3, 4, 8, 12, 16, 20, 32]))
+    R = int(g.choice([1, 3, 3, 3, 5]))
+    stride = int(g.choice([1, 1, 2]))
+    H, W = int(g.integers(max(R, 2), 15)), int(g.integers(max(R, 2), 15))
+    pool = None
+    kind = int(g.integers(0, 4))
+    spec = S(C, H, W, K, A, R=R, stride=stride)
+    if kind == 1 and spec.Ho >= 2 and spec.Wo >= 2:
+        pool = (2, 2, 0)
+    elif kind == 2 and spec.Ho >= 3 and spec.Wo >= 3:
+        pool = (3, 2, 1)
+    skip = 0
+    if pool is None and stride == 1 and kind == 3 and R == 3 and C == K:
+        skip = 1
+    elif pool is None and stride == 1 and kind == 3:
+        skip = 2
+    spec = S(C, H, W, K, A, R=R, stride=stride, pool=pool, skip=skip, skip_C=int(g.choice([4, 8, 6])))
+    return spec, int(g.integers(2, 9)), int(g.choice([2, 10, 37]))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_match_oracle(seed):
+    spec, B, cls = _random_case(seed)
+    print(f"random case {seed}: C={spec.C_in} {spec.H_in}x{spec.W_in} K={spec.C_out} A={spec.A} R={spec.R} "
+          f"stride={spec.stride} pool={spec.pool_kind, spec.pool_k} skip={spec.skip_kind} B={B} cls={cls}", flush=True)
+    # a small learning rate: with a handful of samples a larger one fits the batch in one step, and
+    # the second step's gradient (softmax - onehot ~ 1e-12) is then rounding noise on both sides
+    out, final = G.run_step_both(spec, cls, B, seed=200 + seed, lr=0.002, mu=0.9, steps=2,
+                                 head_pool=seed % 2, loss_kind=(seed // 2) % 2)
+    G.check_step_results(f"random{seed}", out, final)
