@@ -87,9 +87,20 @@ __global__ __launch_bounds__(ET) void maxpool_bwd_kernel(const float *__restrict
       const int v = ww - (jw * ps - pp);
       const int local = u * pk + v;
       const long long o = (((long long)n * Hp + ih) * Wp + jw) * K + kv * V;
+      if constexpr (V == 4) {
+        // one 4-byte and two 16-byte loads, then selects (no per-element branches)
+        const uint32_t a4 = *reinterpret_cast<const uint32_t *>(arg + o);
+        const float4 y4 = *reinterpret_cast<const float4 *>(Y + o);
+        const float4 d4 = *reinterpret_cast<const float4 *>(dY + o);
+        const float yv[4] = {y4.x, y4.y, y4.z, y4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-      for (int e = 0; e < V; ++e)
-        if (arg[o + e] == local && Y[o + e] > 0.f) acc[e] += dY[o + e];
+        for (int e = 0; e < 4; ++e)
+          acc[e] += ((int)((a4 >> (8 * e)) & 0xffu) == local) & (yv[e] > 0.f) ? dv[e] : 0.f;
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (arg[o + e] == local && Y[o + e] > 0.f) acc[e] += dY[o + e];
+      }
     }
   }
   const long long oz = (((long long)n * Ho + hh) * Wo + ww) * K + kv * V;
