@@ -7,6 +7,15 @@ import workloads
 from paper_2402_14139_amd import controller as CT
 
 
+@pytest.fixture(scope="module", autouse=True)
+def _library():
+    import os
+    from paper_2402_14139_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2402_14139_amd import build
+        build.build()
+
+
 def _net():
     """Small ResNet-style network on 16x16 inputs: stem, one basic block per stage, three stages."""
     layers = workloads.resnet_layers([1, 1, 1], widths=(16, 32, 64), in_shape=(3, 16, 16))
