@@ -34,10 +34,11 @@ def test_cfg2_all_layers_small_batch(li):
     _run("cfg2", li, 8, steps=2)
 
 
-@pytest.mark.parametrize("li", [5, 7])
-def test_cfg2_late_layers_full_batch(li):
-    """2x2 .. 4x4 maps at batch 128: few output tiles, so the forward, the head's convolution and
-    the data gradient all run with a split reduction."""
+@pytest.mark.parametrize("li", list(range(8)))
+def test_cfg2_all_layers_full_batch(li):
+    """The VGG-11-style configuration at its own batch size 128.  Its late layers have 2x2 .. 4x4
+    maps: few output tiles, so the forward, the head's convolution and the data gradient all run
+    with a split reduction."""
     _run("cfg2", li, 128)
 
 
