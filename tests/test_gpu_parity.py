@@ -310,3 +310,14 @@ def test_random_shapes_match_oracle(seed):
     out, final = G.run_step_both(spec, cls, B, seed=200 + seed, lr=0.002, mu=0.9, steps=2,
                                  head_pool=seed % 2, loss_kind=(seed // 2) % 2)
     G.check_step_results(f"random{seed}", out, final)
+
+
+@pytest.mark.parametrize("name", ["stride2", "skip_projection", "skinny_a8_c128_split"])
+def test_eight_steps_stay_within_tolerance(name):
+    """Eight consecutive local steps (momentum 0.9) on one batch: the fp32 library and the oracle
+    stay within the tolerance step after step — rounding differences do not accumulate beyond it."""
+    spec, B, cls = CASES[name]
+    out, final = G.run_step_both(spec, cls, B, seed=103, lr=0.005, mu=0.9, steps=8)
+    G.check_step_results(name + "/8steps", out, final)
+    losses = [o[1][0] for o in out]
+    assert losses[-1] < losses[0], losses
