@@ -225,8 +225,9 @@ int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, con
  * both NULL); logits_out (device [B][n_classes]) is optional.
  * nf_block_evaluate: the early-exit model that leaves the block after layer exit_layer: rows
  * [0, n_items) of the block's input cache in batches of B (last one partial), forward through
- * layers 0..exit_layer, that layer's head; pred_out [n_items], *n_correct the total.  The block's
- * aux and ap arrays are required, gp/ga/vp/va are not read.
+ * layers 0..exit_layer, that layer's head; pred_out [n_items], *n_correct the total (cache_labels
+ * and n_correct may both be NULL: plain prediction).  The block's aux and ap arrays are required,
+ * gp/ga/vp/va are not read.
  * nf_select_exit (host): index of the exit with the most correct validation predictions; among
  * equals the one whose model has the fewest parameters; among those the earliest. */
 int32_t nf_aux_predict(const nf_layer_desc *d, const nf_aux_desc *a, int32_t B, const float *y,

@@ -147,3 +147,45 @@ class Trainer:
 
     def select_exit(self, correct, n_params) -> int:
         return nf.nf_select_exit(correct, n_params)
+
+    def predict(self, data, exit_layer: int):
+        """Classes predicted by the early-exit model that ends after layer ``exit_layer`` (global
+        index) for ``data`` [N, C*H*W] (library layout, on the device).  Returns int32 [N]."""
+        torch = self.torch
+        N = data.shape[0]
+        pred = torch.empty((N,), dtype=torch.int32, device=self.device)
+        cache = data
+        for k, plan in enumerate(self.plans):
+            if exit_layer <= plan.last:
+                nf.nf_block_evaluate(self.blocks[k], exit_layer - plan.first, plan.batch, N, cache, None, N, pred,
+                                     None, self.ws[k])
+                return pred
+            dummy = torch.zeros((N,), dtype=torch.int32, device=self.device)
+            cache, _ = self._sweep(k, cache, dummy, N)
+        raise ValueError("exit_layer beyond the network")
+
+    # The Controller keeps idle blocks on a storage device; here that is a plain .npz of all
+    # parameters (and momentum buffers) in the library's layout, keyed by layer index.
+    def save(self, path):
+        out = {}
+        for li, L in enumerate(self.layers):
+            for which in ("p", "v"):
+                src = getattr(L, which)
+                if src is None:
+                    continue
+                for name, tns in src.items():
+                    if tns is not None:
+                        out[f"{which}.{li}.{name}"] = tns.detach().cpu().numpy()
+        np.savez(path, **out)
+
+    def load(self, path):
+        with np.load(path, allow_pickle=False) as z:
+            for li, L in enumerate(self.layers):
+                for which in ("p", "v"):
+                    src = getattr(L, which)
+                    if src is None:
+                        continue
+                    for name, tns in src.items():
+                        key = f"{which}.{li}.{name}"
+                        if tns is not None and key in z:
+                            tns.copy_(self.torch.from_numpy(z[key]).to(self.device))

@@ -252,7 +252,8 @@ int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, con
 int32_t nf_block_evaluate(const nf_block *blk, int32_t exit_layer, int32_t B, int64_t n_items, const float *cache,
                           const int32_t *cache_labels, int64_t capacity, int32_t *pred_out, int32_t *n_correct,
                           void *ws, size_t ws_bytes, void *stream) {
-  if (!blk || !cache || !cache_labels || !pred_out || !n_correct) return NF_ERR_NULL;
+  if (!blk || !cache || !pred_out) return NF_ERR_NULL;
+  if ((cache_labels == nullptr) != (n_correct == nullptr)) return NF_ERR_NULL;  // both, or plain prediction
   if (n_items <= 0 || capacity <= 0 || B <= 0) return NF_ERR_BAD_DESC;
   if (n_items > capacity) return NF_ERR_CACHE_RANGE;
   if (exit_layer < 0 || exit_layer >= blk->n_layers) return NF_ERR_BAD_DESC;
@@ -265,7 +266,7 @@ int32_t nf_block_evaluate(const nf_block *blk, int32_t exit_layer, int32_t B, in
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1)) || ws_bytes < pl.total) return NF_ERR_WORKSPACE;
   for (int64_t j = 0; j < n_batches; ++j) {
     const int32_t nb = j == n_batches - 1 ? B_last : B;
-    int32_t *lab = reinterpret_cast<int32_t *>(at(ws, pl.lab_off[0]));
+    int32_t *lab = cache_labels ? reinterpret_cast<int32_t *>(at(ws, pl.lab_off[0])) : nullptr;
     if ((rc = nf_cache_read(cache, cache_labels, capacity, pl.se_in, j * B, nullptr, nb, at(ws, pl.xin_off[0]), lab,
                             stream)))
       return rc;

@@ -275,6 +275,8 @@ def test_evaluation_calls_validate_before_enqueue(L):
     assert ev(e=len(specs)) == nf.NF_ERR_BAD_DESC
     assert ev(n_items=5 * B) == nf.NF_ERR_CACHE_RANGE
     assert ev(pred_out=None) == nf.NF_ERR_NULL
+    assert L.nf_block_evaluate(C.byref(blk), 0, B, 2 * B, good, None, 4 * B, good, good, good << 8, bneed,
+                               None) == nf.NF_ERR_NULL      # a counter without labels
     assert ev(ws_bytes=bneed // 2) == nf.NF_ERR_WORKSPACE
     out = C.c_int32()
     one = (C.c_int64 * 1)(3)

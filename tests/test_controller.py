@@ -82,3 +82,19 @@ def test_pipeline_learns_a_separable_task():
     e = tr.select_exit(correct, n_params)
     print("plans", plans, "correct", correct, "exit", e, flush=True)
     assert correct[e] == max(correct) and correct[e] >= 0.9 * NV
+    # plain prediction (no labels) agrees with the counted evaluation; a saved and re-loaded network
+    # predicts bit-for-bit the same
+    val = rows[N:].contiguous()
+    pred = tr.predict(val, e)
+    torch.cuda.synchronize()
+    assert int((pred == labels[N:]).sum().item()) == correct[e]
+    import os
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        path = os.path.join(tmp, "net.npz")
+        tr.save(path)
+        fresh = CT.Trainer(specs, cls, [workloads.gen_layer_params(78, i, ls, cls) for i, ls in enumerate(specs)],
+                           plans, momentum=True)
+        fresh.load(path)
+        assert torch.equal(fresh.predict(val, len(specs) - 1), tr.predict(val, len(specs) - 1))
+        assert torch.equal(fresh.predict(val, e), pred)
