@@ -164,6 +164,7 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
     const float *wr = Wf + (long long)q * s.F;
     float acc = 0.f;
     if ((s.F & 3) == 0) {
+#pragma unroll 8
       for (int f = 0; f < s.F; f += 4) {
         const float4 w = *reinterpret_cast<const float4 *>(wr + f);
         acc += w.x * pq[f] + w.y * pq[f + 1] + w.z * pq[f + 2] + w.w * pq[f + 3];
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
   __syncthreads();
   for (int f = t; f < s.F; f += HT) {
     float acc = 0.f;
-#pragma unroll 4
+#pragma unroll 10
     for (int q = 0; q < s.Cls; ++q) acc += z[q] * Wf[(long long)q * s.F + f];
     dPq[(long long)n * s.F + f] = acc;
   }
