@@ -453,11 +453,7 @@ int wgrad_pick_splits(int P, int Q, int M) {
   double best_cost = 1e30;
   for (long long S = 1; S <= max_by_m && S <= 512; ++S) {
     const long long wgs = tiles * S, rounds = (wgs + 511) / 512;
-    // a partly filled last round costs less than a full one (its workgroups run unpaired and
-    // faster, and slots free up unevenly): measured on 152-tile and 144-tile launches, a quarter
-    // of the idle share of the last round is what it costs
-    const double full = (double)(rounds * 512) / (double)wgs, even = wgs >= 512 ? 1.0 : 512.0 / (double)wgs;
-    const double cost = work_us * (0.25 * full + 0.75 * even) + 8.0 * (double)S * P * Q / 3e12 * 1e6;
+    const double cost = work_us * (double)(rounds * 512) / (double)wgs + 8.0 * (double)S * P * Q / 3e12 * 1e6;
     if (cost < best_cost) best_cost = cost, best = S;
   }
   return (int)best;
