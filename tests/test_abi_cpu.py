@@ -182,6 +182,54 @@ def test_block_workspace(L, cfg_name, k):
     assert total == want and total < (16 << 30)
 
 
+@pytest.mark.parametrize("cfg_name", ["cfg4", "cfg5"])
+def test_every_layer_has_a_full_batch_parity_case(cfg_name):
+    """The GPU parity suite runs one representative per distinct (descriptor, head width, batch
+    size); every layer of the configuration must equal its representative field by field."""
+    import workloads
+    from tests.test_gpu_configs import distinct_layers
+    cfg = workloads.config(cfg_name)
+    tested, rep = distinct_layers(cfg_name)
+    assert len(rep) == len(cfg.layers)
+    for i, ls in enumerate(cfg.layers):
+        r = cfg.layers[rep[i]]
+        assert rep[i] in tested and rep[i] <= i
+        assert ls.layer_desc_fields() == r.layer_desc_fields() and ls.A == r.A
+        assert cfg.blocks[ls.block].batch == cfg.blocks[r.block].batch
+
+
+def test_cfg5_blocks_fit_the_memory_budget(L):
+    """The ResNet-34-style configuration sizes its blocks under a fixed 16 GiB budget for
+    activations + weights (the budget M that Algorithm 1 consumes).  Batch sizes are given, so the
+    budget is an assertion: while block k is trained, device memory holds its input cache and the
+    cache it fills for block k+1 (all 16 384 samples, labels included), the block's workspace
+    (double-buffered input batch, every layer's emitted batch, the largest single-layer workspace)
+    and parameters + gradients + momentum buffers of its layers and heads."""
+    import workloads
+    cfg = workloads.config("cfg5")
+    budget, N = cfg.extra["memory_budget_bytes"], cfg.n_samples
+    assert budget == 16 << 30 and N == 16384
+    peak = 0
+    for k, b in enumerate(cfg.blocks):
+        _, _, specs, blk = _cfg_block("cfg5", k)
+        f, last = specs[0], specs[-1]
+        cache_in = N * (4 * f.C_in * f.H_in * f.W_in + 4)
+        cache_out = N * (4 * last.C_out * last.Hp * last.Wp + 4)
+        ws = nf.nf_block_workspace_bytes(blk, b.batch)
+        params = 0
+        for ls in specs:
+            F = 4 * ls.A
+            n = ls.C_out * ls.C_in * ls.R * ls.S + ls.C_out + (ls.C_out * ls.skip_C if ls.skip_kind == 2 else 0)
+            n += ls.A * ls.C_out * 9 + ls.A + cfg.n_classes * F + cfg.n_classes
+            params += 3 * 4 * n                              # weights, gradients, momentum
+        total = cache_in + cache_out + ws + params
+        print(f"cfg5 block {k} (B={b.batch}, {len(specs)} layers): caches {(cache_in + cache_out) / 2**30:.2f} GiB, "
+              f"workspace {ws / 2**30:.3f} GiB, parameters x3 {params / 2**30:.3f} GiB, total {total / 2**30:.2f} GiB")
+        assert total <= budget, (k, total)
+        peak = max(peak, total)
+    assert peak > budget // 4    # the budget is not vacuous: the early blocks use a good part of it
+
+
 def test_block_calls_validate_before_enqueue(L):
     good = 0x10000
     cfg, b, specs, blk = _cfg_block("cfg3", 1)

@@ -86,9 +86,10 @@ def test_block_epoch_matches_oracle(kind, mu, prefetch):
                                 prefetch_stream=side)
     main.synchronize()
 
-    # The oracle's block pass, in lock-step with the same pass issued call by call on the GPU: a
-    # ReLU / max-pool decision that is a tie within rounding is taken as the kernels took it (it
-    # is asserted that the two sides differ nowhere else), so both follow the same trajectory.
+    # The oracle's block pass, in lock-step with the same pass issued call by call on the GPU.  Where
+    # the oracle's own pre-activation is a tie within fp32 rounding, its step takes the admissible
+    # alternative the kernels took (see gpu_common.oracle_step: the kernels' decisions are only
+    # compared, never handed to the oracle), so both follow the same trajectory.
     manual = GpuBlock(specs, skip, cls, params, B, mu != 0)
     obl = []
     for ls, p, s in zip(specs, params, skip):
@@ -99,7 +100,7 @@ def test_block_epoch_matches_oracle(kind, mu, prefetch):
     f = specs[0]
     xbuf = torch.empty((B, f.H_in, f.W_in, f.C_in), device="cuda")
     lbuf = torch.empty((B,), dtype=torch.int32, device="cuda")
-    acts, man_losses, n_tie = [], [], [0]
+    acts, man_losses, ties = [], [], G.TieStats()
 
     def step(j, n, L, x, xs, lb):
         nbj = x.shape[0]
@@ -113,13 +114,12 @@ def test_block_epoch_matches_oracle(kind, mu, prefetch):
         acts.append(y)
         man_losses.append(float(gl.loss.item()))
         dec = G.gpu_decisions(gl, specs[n], nbj, y.cpu().numpy())
-        oy, oloss, _, nt = G.oracle_step(L.d, L.a, specs[n], x, xs, lb, L.params, L.mom, lr, mu, dec)
-        n_tie[0] += nt
+        oy, oloss, _, _ = G.oracle_step(L.d, L.a, specs[n], x, xs, lb, L.params, L.mom, lr, mu, dec, stats=ties)
         return oy, oloss
 
     ref = np.stack([O.block_train_epoch(obl, X.reshape(N, -1), lab, idx, N, B, X.shape[1:], lr, mu, step=step)
                     for _ in range(2)])
-    print(f"  {n_tie[0]} tie decision(s) taken from the kernels", flush=True)
+    print(f"  {ties}", flush=True)
     got = losses.cpu().numpy()
     assert np.array_equal(got.reshape(-1), np.array(man_losses, np.float32)), "block call != call-by-call sequence"
     assert all(torch.equal(a, b) for a, b in zip(gb.state(), manual.state())), "block call != call-by-call sequence"

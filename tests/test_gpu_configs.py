@@ -3,8 +3,9 @@
 * the ResNet-18-style configuration at FULL block batch sizes (64/128/256/512), i.e. in the
   launch configuration bench.py times: every one of its 17 layers, whole local step against
   the oracle;
-* every layer of the VGG-11-style configuration and sampled layers of the VGG-16- and
-  ResNet-34-style ones at a reduced batch (the oracle is a plain loop nest).
+* every layer of the VGG-11-style configuration at a reduced batch (two steps) and at its own;
+* every distinct layer of the VGG-16- and ResNet-34-style configurations at its block's own batch
+  size, plus sampled ones at a reduced batch.
 """
 import pytest
 
@@ -62,12 +63,23 @@ def test_wide_heads_full_batch(cfg_name, li):
     _run(cfg_name, li, cfg.blocks[cfg.layers[li].block].batch)
 
 
-@pytest.mark.parametrize("cfg_name,li", [("cfg4", 0), ("cfg4", 1), ("cfg4", 3), ("cfg4", 6), ("cfg4", 8), ("cfg4", 12),
-                                         ("cfg5", 0), ("cfg5", 1), ("cfg5", 7), ("cfg5", 8), ("cfg5", 15),
-                                         ("cfg5", 16), ("cfg5", 21), ("cfg5", 27), ("cfg5", 28)])
-def test_cfg4_cfg5_sampled_layers_full_batch(cfg_name, li):
+def distinct_layers(cfg_name):
+    """Index of the first layer of every distinct (layer descriptor, head width, block batch size)
+    of a configuration, and for every layer the representative it equals."""
+    cfg = workloads.config(cfg_name)
+    first, rep = {}, []
+    for i, ls in enumerate(cfg.layers):
+        key = (tuple(sorted(ls.layer_desc_fields().items())), ls.A, cfg.blocks[ls.block].batch)
+        rep.append(first.setdefault(key, i))
+    return sorted(set(rep)), rep
+
+
+@pytest.mark.parametrize("cfg_name,li", [(c, i) for c in ("cfg4", "cfg5") for i in distinct_layers(c)[0]])
+def test_cfg4_cfg5_every_layer_full_batch(cfg_name, li):
     """The VGG-16- and ResNet-34-style configurations at their own block batch sizes (32 ... 512):
-    64x64 and 128x128 inputs, the 7x7 stride-2 stem with its 3x3/s2/p1 max-pool, pooled VGG layers,
-    stride-2 and projection-shortcut layers, the 512-sample stage-3 layers."""
+    every layer, one whole local step against the oracle.  Layers that repeat an earlier one exactly
+    (same descriptor, head width and batch size: 1 of 13 and 16 of 33) are represented by it.
+    Covers 64x64 and 128x128 inputs, the 7x7 stride-2 stem with its 3x3/s2/p1 max-pool, pooled VGG
+    layers, stride-2 and projection-shortcut layers, identity shortcuts, the 512-sample stage-3 layers."""
     cfg = workloads.config(cfg_name)
     _run(cfg_name, li, cfg.blocks[cfg.layers[li].block].batch)
