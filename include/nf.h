@@ -26,7 +26,9 @@
  * ---- Ownership, streams, errors -----------------------------------------------------------
  *   The caller owns every buffer, including the workspace `ws` (size from
  *   nf_workspace_bytes, 256-byte aligned).  The library allocates nothing and keeps no
- *   state between calls.  `stream` is a hipStream_t passed as void* (NULL = default
+ *   state between calls (three documented exceptions: the static scratch array of
+ *   nf_local_step_static, the event pool of the prefetch mode of nf_block_train_epoch, and the
+ *   measurement aid nf_prof_begin/end).  `stream` is a hipStream_t passed as void* (NULL = default
  *   stream); every call only enqueues work on it and never synchronises the host.
  *   Every device pointer must be 16-byte aligned.
  *   Every call returns NF_OK (0) or a negative nf_status.  Arguments are validated before
@@ -51,7 +53,8 @@ typedef enum {
   NF_ERR_UNSUPPORTED = -3, /* filter/stride/pool outside what the kernels implement        */
   NF_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or smaller than required          */
   NF_ERR_CACHE_RANGE = -5, /* first + B exceeds the cache capacity                         */
-  NF_ERR_DEVICE = -6       /* a HIP call failed (launch error)                             */
+  NF_ERR_DEVICE = -6,      /* a HIP call failed (launch error)                             */
+  NF_ERR_SCRATCH_LIMIT = -7 /* nf_local_step_static: the step needs more than NF_STATIC_SCRATCH_BYTES */
 } nf_status;
 
 /* Layer n of Eq. 1: conv theta_n (+bias, + optional shortcut), ReLU, optional max-pool P_n.
@@ -164,6 +167,26 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
                       const nf_layer_params *p, const nf_aux_params *ap, const nf_layer_params *gp,
                       const nf_aux_params *ga, const nf_layer_params *vp, const nf_aux_params *va,
                       float *y_out, float *loss_out, void *ws, size_t ws_bytes, void *stream);
+
+/* nf_local_step for callers that cannot allocate device memory or hand in a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-for-bit the same results as nf_local_step, but the scratch lives in a
+ * file-scope device array of NF_STATIC_SCRATCH_BYTES inside the library (one copy per GPU the
+ * library runs on, held until the process ends) instead of a caller workspace.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ * A (layer, head, B) whose nf_workspace_bytes exceeds NF_STATIC_SCRATCH_BYTES is rejected with
+ * NF_ERR_SCRATCH_LIMIT before anything is enqueued (a 512-channel 3x3 layer at batch 512 on 4x4
+ * maps needs 89 MiB, the largest layer of the VGG-16-style workload 115 MiB).
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race; order them on one stream.  The array keeps the previous call's
+ * contents, which is harmless: every region is written by the step before it is read.  The
+ * intermediates nf_workspace_region describes are not reachable through this entry point. */
+#define NF_STATIC_SCRATCH_BYTES (128u << 20)
+int32_t nf_local_step_static(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd_desc *s, int32_t B,
+                             const float *x, const float *x_skip, const int32_t *labels,
+                             const nf_layer_params *p, const nf_aux_params *ap, const nf_layer_params *gp,
+                             const nf_aux_params *ga, const nf_layer_params *vp, const nf_aux_params *va,
+                             float *y_out, float *loss_out, void *stream);
 
 /* ---- a block of consecutive local layers (the paper's partition of the network into blocks,
  * each trained at its own batch size; Worker loop of Algorithm 2; "Efficient Forward Propagation

@@ -16,13 +16,15 @@ LIB_PATH = os.path.join(_HERE, "libnf.so")
 NF_OK = 0
 NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE_RANGE, NF_ERR_DEVICE = (
     -1, -2, -3, -4, -5, -6)
+NF_ERR_SCRATCH_LIMIT = -7
+NF_STATIC_SCRATCH_BYTES = 128 << 20
 
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
            "nf_block_train_epoch", "nf_block_fill_cache", "nf_layer_step_bytes", "nf_fit_linear",
            "nf_profile_layer", "nf_partition", "nf_aux_predict", "nf_block_evaluate", "nf_select_exit",
-           "nf_device_info")
+           "nf_device_info", "nf_local_step_static")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
 NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
@@ -117,6 +119,7 @@ def lib():
                                     C.POINTER(LayerParams), C.POINTER(AuxParams), C.POINTER(LayerParams),
                                     C.POINTER(AuxParams), C.POINTER(LayerParams), C.POINTER(AuxParams),
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nf_local_step_static.argtypes = L.nf_local_step.argtypes[:15] + [C.c_void_p]
         L.nf_prof_end.argtypes = [C.POINTER(ProfRecord), C.c_int32, C.POINTER(C.c_int32)]
         L.nf_workspace_region.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
                                           C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
@@ -252,6 +255,17 @@ def nf_local_step(d, a, lr, momentum, B, x, x_skip, labels, p, ap, gp, ga, vp, v
                                C.byref(p), C.byref(ap), C.byref(gp), C.byref(ga),
                                C.byref(vp) if vp is not None else None, C.byref(va) if va is not None else None,
                                _ptr(y_out), _ptr(loss_out), wp, wn, _stream(stream)), "nf_local_step")
+
+
+def nf_local_step_static(d, a, lr, momentum, B, x, x_skip, labels, p, ap, gp, ga, vp, va, y_out, loss_out,
+                         stream=None):
+    """nf_local_step with the scratch in the library's static device array (allocates nothing)."""
+    s = SgdDesc(lr, momentum)
+    _check(lib().nf_local_step_static(C.byref(d), C.byref(a), C.byref(s), B, _ptr(x), _ptr(x_skip), _ptr(labels),
+                                      C.byref(p), C.byref(ap), C.byref(gp), C.byref(ga),
+                                      C.byref(vp) if vp is not None else None,
+                                      C.byref(va) if va is not None else None,
+                                      _ptr(y_out), _ptr(loss_out), _stream(stream)), "nf_local_step_static")
 
 
 def nf_prof_begin():

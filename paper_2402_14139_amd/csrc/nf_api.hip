@@ -5,9 +5,14 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "nf_internal.h"
+
+// Scratch of nf_local_step_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[NF_STATIC_SCRATCH_BYTES];
 
 namespace nf {
 namespace {
@@ -464,6 +469,68 @@ int32_t check_pair(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
   return NF_OK;
 }
 
+// Device address of `scratch` on the current device: looked up once per device (each GPU holds
+// its own copy at its own address) and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];
+
+int32_t static_scratch(void **out) {
+  int dev = -1;
+  NF_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return NF_ERR_DEVICE;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    NF_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return NF_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return NF_OK;
+}
+
+// nf_local_step with the workspace given (ws != nullptr) or taken from the static array
+int32_t local_step_impl(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd_desc *s, int32_t B,
+                        const float *x, const float *x_skip, const int32_t *labels, const nf_layer_params *p,
+                        const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga,
+                        const nf_layer_params *vp, const nf_aux_params *va, float *y_out, float *loss_out,
+                        void *ws, size_t ws_bytes, bool use_static, void *stream) {
+  LayerDims ld;
+  AuxDims ad;
+  int32_t rc = check_layer(d, &ld);
+  if (rc) return rc;
+  if ((rc = check_aux(a, &ad))) return rc;
+  if ((rc = check_pair(d, ld, a))) return rc;
+  if ((rc = check_sizes(d, ld, B))) return rc;
+  if (!s || !labels || !y_out || !loss_out) return NF_ERR_NULL;
+  if ((rc = check_layer_ptrs(d, x, x_skip, p))) return rc;
+  if ((rc = check_aux_ptrs(ap))) return rc;
+  if ((rc = check_layer_ptrs(d, x, x_skip, gp))) return rc;
+  if ((rc = check_aux_ptrs(ga))) return rc;
+  if (s->momentum != 0.f) {
+    if (!vp || !va) return NF_ERR_NULL;
+    if ((rc = check_layer_ptrs(d, x, x_skip, vp))) return rc;
+    if ((rc = check_aux_ptrs(va))) return rc;
+  }
+  if (!aligned16(y_out)) return NF_ERR_BAD_DESC;
+  const WsLayout w = ws_layout(d, ld, a, ad, B);
+  if (use_static) {
+    if (w.total > (size_t)NF_STATIC_SCRATCH_BYTES) return NF_ERR_SCRATCH_LIMIT;
+    if ((rc = static_scratch(&ws))) return rc;
+  } else if ((rc = check_ws(ws, ws_bytes, w.total))) {
+    return rc;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // Algorithm 2: forward with the current weights (this y_out is what the next layer reads),
+  // head + loss, local gradients, update.
+  if ((rc = run_layer_fwd(d, ld, B, x, x_skip, p, y_out, ws, w, st))) return rc;
+  // the batch-mean loss rides on the head's backward launch
+  if ((rc = run_aux_fwd(a, ad, B, y_out, labels, ap, nullptr, ws, w, st))) return rc;
+  // ... and the update on the launch that finishes the weight gradients
+  return run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, loss_out, s, vp, va, ws, w, st);
+}
+
 }  // namespace
 }  // namespace nf
 
@@ -480,6 +547,7 @@ const char *nf_strerror(int32_t s) {
     case NF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case NF_ERR_CACHE_RANGE: return "cache range exceeds capacity";
     case NF_ERR_DEVICE: return "HIP error while enqueueing";
+    case NF_ERR_SCRATCH_LIMIT: return "the step needs more scratch than the static buffer of nf_local_step_static holds";
     default: return "unknown status";
   }
 }
@@ -677,34 +745,17 @@ int32_t nf_local_step(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd
                       const nf_aux_params *ap, const nf_layer_params *gp, const nf_aux_params *ga,
                       const nf_layer_params *vp, const nf_aux_params *va, float *y_out, float *loss_out,
                       void *ws, size_t ws_bytes, void *stream) {
-  LayerDims ld;
-  AuxDims ad;
-  int32_t rc = check_layer(d, &ld);
-  if (rc) return rc;
-  if ((rc = check_aux(a, &ad))) return rc;
-  if ((rc = check_pair(d, ld, a))) return rc;
-  if ((rc = check_sizes(d, ld, B))) return rc;
-  if (!s || !labels || !y_out || !loss_out) return NF_ERR_NULL;
-  if ((rc = check_layer_ptrs(d, x, x_skip, p))) return rc;
-  if ((rc = check_aux_ptrs(ap))) return rc;
-  if ((rc = check_layer_ptrs(d, x, x_skip, gp))) return rc;
-  if ((rc = check_aux_ptrs(ga))) return rc;
-  if (s->momentum != 0.f) {
-    if (!vp || !va) return NF_ERR_NULL;
-    if ((rc = check_layer_ptrs(d, x, x_skip, vp))) return rc;
-    if ((rc = check_aux_ptrs(va))) return rc;
-  }
-  if (!aligned16(y_out)) return NF_ERR_BAD_DESC;
-  const WsLayout w = ws_layout(d, ld, a, ad, B);
-  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  // Algorithm 2: forward with the current weights (this y_out is what the next layer reads),
-  // head + loss, local gradients, update.
-  if ((rc = run_layer_fwd(d, ld, B, x, x_skip, p, y_out, ws, w, st))) return rc;
-  // the batch-mean loss rides on the head's backward launch
-  if ((rc = run_aux_fwd(a, ad, B, y_out, labels, ap, nullptr, ws, w, st))) return rc;
-  // ... and the update on the launch that finishes the weight gradients
-  return run_bwd(d, ld, a, ad, B, x, x_skip, y_out, p, ap, gp, ga, loss_out, s, vp, va, ws, w, st);
+  return local_step_impl(d, a, s, B, x, x_skip, labels, p, ap, gp, ga, vp, va, y_out, loss_out, ws, ws_bytes, false,
+                         stream);
+}
+
+int32_t nf_local_step_static(const nf_layer_desc *d, const nf_aux_desc *a, const nf_sgd_desc *s, int32_t B,
+                             const float *x, const float *x_skip, const int32_t *labels,
+                             const nf_layer_params *p, const nf_aux_params *ap, const nf_layer_params *gp,
+                             const nf_aux_params *ga, const nf_layer_params *vp, const nf_aux_params *va,
+                             float *y_out, float *loss_out, void *stream) {
+  return local_step_impl(d, a, s, B, x, x_skip, labels, p, ap, gp, ga, vp, va, y_out, loss_out, nullptr, 0, true,
+                         stream);
 }
 
 int32_t nf_device_info(int32_t *compute_units, int32_t *clock_khz) {

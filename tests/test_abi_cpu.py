@@ -149,9 +149,36 @@ def test_calls_validate_before_enqueue(L):
 
 def test_strerror(L):
     assert nf.strerror(0) == "ok"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert nf.strerror(code) and nf.strerror(code) != "unknown status"
     assert nf.strerror(-99) == "unknown status"
+
+
+def test_static_scratch_entry_point_validates_and_rejects_oversize(L):
+    """nf_local_step_static validates like nf_local_step and rejects a step whose workspace
+    exceeds the static array, all before any device work (so it is checkable without a GPU)."""
+    good = 0x10000
+    p, ap = nf.LayerParams(good, good, None), nf.AuxParams(good, good, good, good)
+    s = nf.SgdDesc(0.01, 0.0)
+
+    def call(d, a, B, x=good, labels=good, y=good, loss=good):
+        return L.nf_local_step_static(C.byref(d), C.byref(a), C.byref(s), B, x, None, labels, C.byref(p), C.byref(ap),
+                                      C.byref(p), C.byref(ap), None, None, y, loss, None)
+
+    d = _layer(C_in=64, H_in=64, W_in=64, C_out=64)
+    a = _aux(C_in=64, H_in=64, W_in=64, A=64, n_classes=200)
+    need = nf.nf_workspace_bytes(d, a, 64)
+    assert need > nf.NF_STATIC_SCRATCH_BYTES
+    assert call(d, a, 64) == nf.NF_ERR_SCRATCH_LIMIT
+    assert "static" in nf.strerror(nf.NF_ERR_SCRATCH_LIMIT)
+    small_d, small_a = _layer(), _aux()
+    assert nf.nf_workspace_bytes(small_d, small_a, 4) <= nf.NF_STATIC_SCRATCH_BYTES
+    assert call(small_d, small_a, 4, x=None) == nf.NF_ERR_NULL
+    assert call(small_d, small_a, 4, y=good + 4) == nf.NF_ERR_BAD_DESC
+    assert call(small_d, small_a, 0) == nf.NF_ERR_BAD_DESC
+    text = open(os.path.join(ROOT, "include", "nf.h")).read()
+    m = re.search(r"#define NF_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == nf.NF_STATIC_SCRATCH_BYTES
 
 
 # ---- block-level calls: everything below fails (or only sizes things) before any enqueue ----------
