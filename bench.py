@@ -35,6 +35,16 @@ TRAFFIC_BYTES_PER_LAUNCH = {
     ("cfg3_resnet18", "igemm_wgrad_fast_128x128"): 66.5e6 + 37.9e6,
     ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 67.4e6 + 16.8e6,
 }
+TRAFFIC_SOURCE = ("offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this script, scaled by a 1 GiB copy "
+                  "(FETCH x 2.0, WRITE x 1.0); summary in profiles/local_step_cfg3_hbm_traffic.md; not re-measured "
+                  "by this run")
+# The same counters for the HBM-bound kernels of the default workload (bytes per launch, averaged over
+# the launches of one step; same two passes, same scaling).  None: not collected for that kernel.
+HBM_COUNTER_BYTES_PER_LAUNCH = {
+}
+# kernels judged against the HBM roofline (everything that is not a contraction)
+HBM_KERNELS = ("cache_read", "cache_write", "cache_copy", "wgrad_reduce_sgd", "wgrad_reduce", "head_pool", "head_fc",
+               "head_fwd", "head_bwd", "maxpool_fwd", "maxpool_bwd", "fwd_finish", "sgd", "loss_mean")
 
 
 def layer_flops(ls, B, n_classes):
@@ -216,7 +226,7 @@ def main():
         f"{flops_per_step / dt * args.steps / 1e12:.2f} TFLOP/s")
 
     # ---- per-kernel timing with HIP events: the same steps again ------------------------------
-    roofline, kernels = None, []
+    roofline, kernels, hbm = None, [], []
     if not args.no_prof:
         psteps = min(args.steps, 5)
         nf.nf_prof_begin()
@@ -236,6 +246,7 @@ def main():
             roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": round(ach, 2),
                         "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_F32_PEAK_TFLOPS, 4),
                         "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, dom["kernel"])),
+                        "traffic_source": TRAFFIC_SOURCE,
                         "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                         "measured_over": f"{psteps} further steps with one HIP-event pair per kernel launch"}
         else:
@@ -244,6 +255,17 @@ def main():
                         "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
                         "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                         "measured_over": f"{psteps} further steps with one HIP-event pair per kernel launch"}
+        # HBM-bound kernels: algorithmic bytes (the library's per-launch formula) / HIP-event duration
+        # against the published 8 TB/s; counter bytes per launch where an offline pass collected them
+        for r in recs:
+            if r["kernel"] in HBM_KERNELS and r["ms"] > 0:
+                gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9
+                hbm.append({"kernel": r["kernel"], "launches_per_step": r["launches"] / psteps,
+                            "algorithmic_bytes_per_launch": round(r["bytes"] / r["launches"]),
+                            "counter_bytes_per_launch": HBM_COUNTER_BYTES_PER_LAUNCH.get((cfg.name, r["kernel"])),
+                            "avg_us": round(1e3 * r["ms"] / r["launches"], 2), "achieved_gbs": round(gbs, 1),
+                            "frac_of_8tbs": round(gbs / HBM_PEAK_GBS, 4),
+                            "ms_per_step": round(r["ms"] / psteps, 4)})
         for kr in kernels:
             log(f"[kernel] {kr['kernel']:<26} {kr['launches_per_step']:6.1f}/step {kr['ms_per_step']:9.4f} ms "
                 f"{100 * kr['share']:5.1f}%  avg {kr['avg_us']:9.2f} us  {kr['tflops']:7.2f} TFLOP/s {kr['gbs']:8.1f} GB/s")
@@ -414,13 +436,44 @@ def main():
                 cur = Y
                 done.append(li)
         scaled_step_s = t_cpu * flops_per_step / fl_sample
-        cpu = {"value": round(images_per_step / scaled_step_s, 3), "unit": "images/s", "cores": O.num_threads(),
+        # the same oracle on ONE thread: the first layers of the step until about 8 s are spent
+        nthreads = O.num_threads()
+        O.set_num_threads(1)
+        t1, fl1, done1 = 0.0, 0.0, []
+        blk0 = cfg.blocks[0]
+        f0 = cfg.layers[blk0.layers[0]]
+        x1 = gcpu.standard_normal((blk0.batch, f0.C_in, f0.H_in, f0.W_in)).astype(np.float32)
+        y1 = gcpu.integers(0, cls, size=(blk0.batch,)).astype(np.int32)
+        cur1, outs1 = x1, {}
+        for li in blk0.layers:
+            if t1 >= 8.0:
+                break
+            ls = cfg.layers[li]
+            pr = workloads.gen_layer_params(cfg.seed, li, ls, cls)
+            xs = None
+            if ls.skip_kind:
+                xs = x1 if ls.skip_src == blk0.layers[0] else outs1[ls.skip_src - 1]
+            od, oa = O.layer_desc(**ls.layer_desc_fields()), O.aux_desc(**ls.aux_desc_fields(cls))
+            t0 = time.perf_counter()
+            Y, _, _ = O.local_step(od, oa, cur1, xs, y1, pr, None, cfg.lr, 0.0)
+            t1 += time.perf_counter() - t0
+            fl1 += layer_flops(ls, blk0.batch, cls)
+            outs1[li] = Y
+            cur1 = Y
+            done1.append(li)
+        O.set_num_threads(nthreads)
+        cpu = {"value": round(images_per_step / scaled_step_s, 3), "unit": "images/s", "cores": nthreads,
                "kind": "oracle",
+               "value_1thread": round(images_per_step / (t1 * flops_per_step / fl1), 3),
+               "gflops_1thread": round(fl1 / t1 / 1e9, 2),
+               "sample_1thread": f"one local step of layers {done1[0]}..{done1[-1]} at batch {blk0.batch} "
+                                 f"({fl1 / 1e9:.1f} GFLOP) took {t1:.2f} s on one thread; scaled by FLOPs",
                "sample": f"one local step of layers {done[0]}..{done[-1]} of {cfg.name} at their block batch sizes "
                          f"({fl_sample / 1e9:.1f} of the step's {flops_per_step / 1e9:.1f} GFLOP) took {t_cpu:.2f} s; "
                          f"scaled by FLOPs to the full step",
                "gflops": round(fl_sample / t_cpu / 1e9, 2)}
-        log(f"[cpu] oracle {t_cpu:.2f}s on {O.num_threads()} threads, {fl_sample / t_cpu / 1e9:.2f} GFLOP/s")
+        log(f"[cpu] oracle {t_cpu:.2f}s on {nthreads} threads, {fl_sample / t_cpu / 1e9:.2f} GFLOP/s; "
+            f"one thread {fl1 / t1 / 1e9:.2f} GFLOP/s")
 
     tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
     out = {
@@ -436,7 +489,7 @@ def main():
                    "gflop_per_step": round(flops_per_step / 1e9, 1)},
         "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
         "losses_finite": finite,
-        "roofline": roofline, "cpu_baseline": cpu, "block_driver": block_driver, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "hbm": hbm, "block_driver": block_driver, "kernels": kernels,
         "layers": per_layer, "blocks": per_block, "device": device,
     }
     print(json.dumps(out), flush=True)

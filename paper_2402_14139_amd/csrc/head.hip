@@ -4,12 +4,14 @@
 // three (gradient line of Algorithm 2).
 // These steps are tiny next to the convolutions; they are written as fused wavefront /
 // workgroup reductions with a fixed summation order (deterministic).
+#include "head_gamma.h"
 #include "nf_internal.h"
 
 namespace nf {
 namespace {
 
 constexpr int HT = 256;  // threads per workgroup in this file
+static_assert(HT == GJ_T, "the batch-reducing jobs assume this workgroup size");
 
 __device__ inline void adaptive_window(int i, int L, int O, int &lo, int &hi) {
   lo = (i * L) / O;
@@ -34,20 +36,20 @@ __device__ inline float wave_max(float v) {
 // through LDS.
 // With splits > 0 the aux activation does not exist yet: it is formed here from the raw partial
 // sums of the split aux convolution, U = act(sum_z part[z] + ba), and written out on the way.
+// (all threads of a workgroup; pairs [pair0, pair0 + G) below pair_end; red / redi: HT*V entries of
+// LDS; pq_lds / parg_lds, when given, also receive the results at index (pair - lds_pair0) * A + channel)
 template <int V, bool PMAX>
-__global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__restrict__ U,
-                                                       const float *__restrict__ part, int splits,
-                                                       const float *__restrict__ ba, float *__restrict__ Pq,
-                                                       int32_t *__restrict__ parg, int CA, int NS) {
-  __shared__ float red[HT * V];
-  __shared__ int redi[PMAX ? HT * V : 1];
+__device__ inline void pool_pairs(const HeadShape &s, long long pair0, long long pair_end, float *__restrict__ U,
+                                  const float *__restrict__ part, int splits, const float *__restrict__ ba,
+                                  float *__restrict__ Pq, int32_t *__restrict__ parg, int CA, int NS, float *red,
+                                  int *redi, float *pq_lds, int *parg_lds, long long lds_pair0) {
   const int t = threadIdx.x;
   const int per = CA * NS, G = HT / per;
   const int grp = t / per, tg = t - grp * per;
   const int lane = tg % CA, slice = tg / CA;
   const int cells = s.oh * s.ow;
-  const long long pair = (long long)blockIdx.x * G + grp;
-  const bool live = grp < G && pair < (long long)s.B * cells;
+  const long long pair = pair0 + grp;
+  const bool live = grp < G && pair < pair_end;
   const int n = live ? (int)(pair / cells) : 0, cell = live ? (int)(pair - (long long)n * cells) : 0;
   const int ci = cell / s.ow, cj = cell - ci * s.ow;
   int h0, h1, w0, w1;
@@ -134,32 +136,43 @@ __global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__res
           }
           Pq[o] = best;
           parg[o] = bp;
+          if (pq_lds) {
+            const int li = (int)(pair - lds_pair0) * s.A + col * V + e;
+            pq_lds[li] = best, parg_lds[li] = bp;
+          }
         } else {
           float sum = acc[e];
           for (int k = 1; k < NS; ++k) sum += red[(grp * per + k * CA + lane) * V + e];
           Pq[o] = sum * inv;
+          if (pq_lds) pq_lds[(int)(pair - lds_pair0) * s.A + col * V + e] = sum * inv;
         }
       }
     }
   }
 }
 
-// gamma_n and Eq. 3 for one sample per workgroup: logits (one thread per class, the pooled
-// features staged in LDS), log-sum-exp, per-sample loss, dL/dz, and -- the sample's dz being at
-// hand -- the gradient w.r.t. the pooled features dPq[n][f] = sum_q dz[n][q] * Wf[q][f].
-// Dynamic LDS: F + Cls + 8 floats.
-__global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *__restrict__ Pq,
-                                                     const int32_t *__restrict__ labels,
-                                                     const float *__restrict__ Wf, const float *__restrict__ bf,
-                                                     float *__restrict__ dz, float *__restrict__ loss_n,
-                                                     float *__restrict__ dPq) {
-  extern __shared__ float sm[];
-  float *pq = sm;           // [F]
-  float *z = pq + s.F;      // [Cls]
-  float *red = z + s.Cls;   // [8]
-  const int n = blockIdx.x, t = threadIdx.x;
-  for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
-  __syncthreads();
+template <int V, bool PMAX>
+__global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__restrict__ U,
+                                                       const float *__restrict__ part, int splits,
+                                                       const float *__restrict__ ba, float *__restrict__ Pq,
+                                                       int32_t *__restrict__ parg, int CA, int NS) {
+  __shared__ float red[HT * V];
+  __shared__ int redi[PMAX ? HT * V : 1];
+  const int G = HT / (CA * NS);
+  pool_pairs<V, PMAX>(s, (long long)blockIdx.x * G, (long long)s.B * s.oh * s.ow, U, part, splits, ba, Pq, parg, CA, NS,
+                      red, redi, nullptr, nullptr, 0);
+}
+
+// gamma_n and Eq. 3 for one sample (all threads of a workgroup): logits (one thread per class, the
+// pooled features pq[F] already staged in LDS), log-sum-exp, per-sample loss, dL/dz, and -- the
+// sample's dz being at hand -- the gradient w.r.t. the pooled features
+// dPq[f] = sum_q dz[q] * Wf[q][f], stored to dPq_out (global row of the sample, or an LDS array).
+// z: Cls floats of LDS, red: 8 floats of LDS.
+__device__ inline void fc_loss_sample(const HeadShape &s, int n, const float *pq, float *z, float *red,
+                                      const int32_t *__restrict__ labels, const float *__restrict__ Wf,
+                                      const float *__restrict__ bf, float *__restrict__ dz,
+                                      float *__restrict__ loss_n, float *dPq_out) {
+  const int t = threadIdx.x;
   for (int q = t; q < s.Cls; q += HT) {
     const float *wr = Wf + (long long)q * s.F;
     float acc = 0.f;
@@ -197,7 +210,7 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
       float acc = 0.f;
 #pragma unroll 4
       for (int q = 0; q < s.Cls; ++q) acc += z[q] * Wf[(long long)q * s.F + f];
-      dPq[(long long)n * s.F + f] = acc;
+      dPq_out[f] = acc;
     }
     return;
   }
@@ -229,8 +242,24 @@ __global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *_
     float acc = 0.f;
 #pragma unroll 10
     for (int q = 0; q < s.Cls; ++q) acc += z[q] * Wf[(long long)q * s.F + f];
-    dPq[(long long)n * s.F + f] = acc;
+    dPq_out[f] = acc;
   }
+}
+
+// One sample per workgroup.  Dynamic LDS: F + Cls + 8 floats.
+__global__ __launch_bounds__(HT) void head_fc_kernel(HeadShape s, const float *__restrict__ Pq,
+                                                     const int32_t *__restrict__ labels,
+                                                     const float *__restrict__ Wf, const float *__restrict__ bf,
+                                                     float *__restrict__ dz, float *__restrict__ loss_n,
+                                                     float *__restrict__ dPq) {
+  extern __shared__ float sm[];
+  float *pq = sm;           // [F]
+  float *z = pq + s.F;      // [Cls]
+  float *red = z + s.Cls;   // [8]
+  const int n = blockIdx.x, t = threadIdx.x;
+  for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
+  __syncthreads();
+  fc_loss_sample(s, n, pq, z, red, labels, Wf, bf, dz, loss_n, dPq + (long long)n * s.F);
 }
 
 // The same step for wide heads (many pooled features): G samples per workgroup share every load
@@ -397,22 +426,115 @@ __global__ __launch_bounds__(HT) void count_hits_kernel(const int32_t *__restric
   if (threadIdx.x == 0) *out = (accumulate ? *out : 0) + red[0];
 }
 
-// batch mean of the per-sample losses, fixed order (one workgroup)
-__device__ inline void loss_mean_block(const float *__restrict__ loss_n, int B, float *__restrict__ out, float *red) {
-  float acc = 0.f;
-  for (int i = threadIdx.x; i < B; i += HT) acc += loss_n[i];
-  red[threadIdx.x] = acc;
-  __syncthreads();
-  for (int o = HT / 2; o > 0; o >>= 1) {
-    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) *out = red[0] / (float)B;
-}
 __global__ __launch_bounds__(HT) void loss_mean_kernel(const float *__restrict__ loss_n, int B,
                                                        float *__restrict__ out) {
   __shared__ float red[HT];
   loss_mean_block(loss_n, B, out, red);
+}
+
+// dU for V consecutive channels of one element (n, hh, w, av): F_n backward + aux ReLU mask.
+// dpq points at the sample's dPq[F] (global or LDS), pargn at its selection record (max pooling).
+template <int V>
+__device__ inline void du_element(const HeadShape &s, int hh, int w, int av, const float *__restrict__ u_at,
+                                  const float *dpq, const int32_t *pargn, float *__restrict__ du_at) {
+  float u[V], acc[V];
+  if constexpr (V == 4) {
+    const float4 t4 = *reinterpret_cast<const float4 *>(u_at);
+    u[0] = t4.x, u[1] = t4.y, u[2] = t4.z, u[3] = t4.w;
+  } else {
+    u[0] = u_at[0];
+  }
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  for (int ci = 0; ci < s.oh; ++ci) {
+    int h0, h1;
+    adaptive_window(ci, s.Hu, s.oh, h0, h1);
+    if (hh < h0 || hh >= h1) continue;
+    for (int cj = 0; cj < s.ow; ++cj) {
+      int w0, w1;
+      adaptive_window(cj, s.Wu, s.ow, w0, w1);
+      if (w < w0 || w >= w1) continue;
+      const int fo = (ci * s.ow + cj) * s.A + av * V;
+      const float *src = dpq + fo;
+      if (s.pmax) {  // max pooling hands the gradient to the element it selected
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (pargn[fo + e] == hh * s.Wu + w) acc[e] += src[e];
+      } else {
+        const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < V; ++e)
+    if (s.relu && !(u[e] > 0.f)) acc[e] = 0.f;
+  if constexpr (V == 4) {
+    *reinterpret_cast<float4 *>(du_at) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  } else {
+    du_at[0] = acc[0];
+  }
+}
+
+// element i of the re-laid aux filter: WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k]
+__device__ inline void wat_element(long long i, int A, int R, int S, int K, const float *__restrict__ Wa,
+                                   float *__restrict__ WaT) {
+  const int a = (int)(i % A);
+  long long r = i / A;
+  const int sx = (int)(r % S);
+  r /= S;
+  const int rr = (int)(r % R);
+  const int k = (int)(r / R);
+  WaT[i] = Wa[(((long long)a * R + (R - 1 - rr)) * S + (S - 1 - sx)) * K + k];
+}
+
+// The whole per-sample chain of a head with a small activation map in one launch: workgroup n
+// (n < B) runs F_n, gamma_n, the loss and dL/dz, dPq and the backward through F_n and the aux ReLU
+// for sample n; the pooled features, dPq and the max-pooling selection stay in LDS between the
+// stages.  With splits > 0 the aux activation is first formed from the raw partial sums of the
+// split aux convolution (see pool_pairs).  Workgroups from B on re-lay the aux filter for the
+// data gradient.
+// Dynamic LDS: 2*F + Cls + 8 floats, + F ints for max pooling.
+template <int V, bool PMAX>
+__global__ __launch_bounds__(HT) void head_sample_kernel(HeadShape s, float *__restrict__ U,
+                                                         const float *__restrict__ part, int splits,
+                                                         const float *__restrict__ ba,
+                                                         const int32_t *__restrict__ labels,
+                                                         const float *__restrict__ Wf, const float *__restrict__ bf,
+                                                         float *__restrict__ Pq, int32_t *__restrict__ parg,
+                                                         float *__restrict__ dz, float *__restrict__ loss_n,
+                                                         float *__restrict__ dU, const float *__restrict__ Wa,
+                                                         float *__restrict__ WaT, int R, int S, int K, int CA, int NS) {
+  extern __shared__ float sm[];
+  __shared__ float red[HT * V];
+  __shared__ int redi[PMAX ? HT * V : 1];
+  const int t = threadIdx.x;
+  if ((int)blockIdx.x >= s.B) {
+    const long long i = (long long)(blockIdx.x - s.B) * HT + t;
+    if (i < (long long)s.A * R * S * K) wat_element(i, s.A, R, S, K, Wa, WaT);
+    return;
+  }
+  float *pq = sm;            // [F]
+  float *dpq = pq + s.F;     // [F]
+  float *z = dpq + s.F;      // [Cls]
+  float *red8 = z + s.Cls;   // [8]
+  int *pargl = reinterpret_cast<int *>(red8 + 8);  // [F] (max pooling)
+  const int n = blockIdx.x;
+  const int cells = s.oh * s.ow, G = HT / (CA * NS);
+  for (int c0 = 0; c0 < cells; c0 += G)
+    pool_pairs<V, PMAX>(s, (long long)n * cells + c0, (long long)(n + 1) * cells, U, part, splits, ba, Pq, parg, CA,
+                        NS, red, redi, pq, PMAX ? pargl : nullptr, (long long)n * cells);
+  __syncthreads();  // (with splits > 0 the sample's U was formed and written on the way: visible to the workgroup)
+  fc_loss_sample(s, n, pq, z, red8, labels, Wf, bf, dz, loss_n, dpq);
+  __syncthreads();
+  const int AV = s.A / V, per_n = s.Hu * s.Wu * AV;
+  const long long base = (long long)n * per_n;
+  for (int i = t; i < per_n; i += HT) {
+    const int av = i % AV, r = i / AV;
+    const int w = r % s.Wu, hh = r / s.Wu;
+    du_element<V>(s, hh, w, av, U + (base + i) * V, dpq, PMAX ? pargl : nullptr, dU + (base + i) * V);
+  }
 }
 
 // Backward of the head after the softmax in one launch (gradient line of Algorithm 2); the
@@ -442,30 +564,11 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
   int b = blockIdx.x;
   const int t = threadIdx.x;
   if (b < jb.nb_w) {
-    const int fch = jb.fch, nchunks = jb.nchunks;
-    const int q = b / nchunks, chunk = b - q * nchunks;
-    const int fl = t % fch, ns = t / fch, NS = HT / fch;
-    const int f = chunk * fch + fl;
-    float acc = 0.f, bsum = 0.f;
-    if (f < s.F) {
-#pragma unroll 4
-      for (int n = ns; n < s.B; n += NS) {
-        const float d = dz[(long long)n * s.Cls + q];
-        bsum += d;
-        acc += d * Pq[(long long)n * s.F + f];
-      }
-    }
-    red[t] = acc;
-    redb[t] = bsum;
-    __syncthreads();
-    if (ns == 0 && f < s.F) {
-      for (int k = 1; k < NS; ++k) acc += red[k * fch + fl];
-      dWf[(long long)q * s.F + f] = acc;
-    }
-    if (t == 0 && chunk == 0) {
-      for (int k = 1; k < NS; ++k) bsum += redb[k * fch];
-      dbf[q] = bsum;
-    }
+    GammaJob g;
+    g.B = s.B, g.F = s.F, g.Cls = s.Cls, g.Pq = Pq, g.dz = dz, g.dWf = dWf, g.dbf = dbf;
+    g.Wf = g.bf = g.vWf = g.vbf = nullptr, g.lr = g.mu = 0.f;
+    g.fch = jb.fch, g.nchunks = jb.nchunks;
+    gamma_block(g, b, red, redb);
     return;
   }
   b -= jb.nb_w;
@@ -480,45 +583,8 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
     r /= s.Wu;
     const int hh = (int)(r % s.Hu);
     const int n = (int)(r / s.Hu);
-    const long long e0 = i * V;
-    float u[V], acc[V];
-    if constexpr (V == 4) {
-      const float4 t4 = *reinterpret_cast<const float4 *>(U + e0);
-      u[0] = t4.x, u[1] = t4.y, u[2] = t4.z, u[3] = t4.w;
-    } else {
-      u[0] = U[e0];
-    }
-#pragma unroll
-    for (int e = 0; e < V; ++e) acc[e] = 0.f;
-    for (int ci = 0; ci < s.oh; ++ci) {
-      int h0, h1;
-      adaptive_window(ci, s.Hu, s.oh, h0, h1);
-      if (hh < h0 || hh >= h1) continue;
-      for (int cj = 0; cj < s.ow; ++cj) {
-        int w0, w1;
-        adaptive_window(cj, s.Wu, s.ow, w0, w1);
-        if (w < w0 || w >= w1) continue;
-        const long long fo = (long long)n * s.F + (ci * s.ow + cj) * s.A + av * V;
-        const float *src = dPq + fo;
-        if (s.pmax) {  // max pooling hands the gradient to the element it selected
-#pragma unroll
-          for (int e = 0; e < V; ++e)
-            if (parg[fo + e] == hh * s.Wu + w) acc[e] += src[e];
-        } else {
-          const float inv = 1.f / (float)((h1 - h0) * (w1 - w0));
-#pragma unroll
-          for (int e = 0; e < V; ++e) acc[e] += src[e] * inv;
-        }
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < V; ++e)
-      if (s.relu && !(u[e] > 0.f)) acc[e] = 0.f;
-    if constexpr (V == 4) {
-      *reinterpret_cast<float4 *>(dU + e0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    } else {
-      dU[e0] = acc[0];
-    }
+    du_element<V>(s, hh, w, av, U + i * V, dPq + (long long)n * s.F, s.pmax ? parg + (long long)n * s.F : nullptr,
+                  dU + i * V);
     return;
   }
   b -= jb.nb_u;
@@ -526,13 +592,7 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
     const long long total = (long long)s.A * R * S * K;
     const long long i = (long long)b * HT + t;
     if (i >= total) return;
-    const int a = (int)(i % s.A);
-    long long r = i / s.A;
-    const int sx = (int)(r % S);
-    r /= S;
-    const int rr = (int)(r % R);
-    const int k = (int)(r / R);
-    WaT[i] = Wa[(((long long)a * R + (R - 1 - rr)) * S + (S - 1 - sx)) * K + k];
+    wat_element(i, s.A, R, S, K, Wa, WaT);
     return;
   }
   loss_mean_block(loss_n, s.B, loss_out, red);
@@ -540,9 +600,8 @@ __global__ __launch_bounds__(HT) void head_bwd_kernel(HeadShape s, HeadBwdJobs j
 
 }  // namespace
 
-hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
-                            int32_t *parg, hipStream_t st) {
-  const int V = h.A % 4 == 0 ? 4 : 1;
+// pooling decomposition of a workgroup (see pool_pairs): channel lanes CA, position slices NS
+static void pool_lanes(const HeadShape &h, int V, int *CA_out, int *NS_out) {
   const int AV = h.A / V;
   int CA = 1;
   while (CA < AV && CA < HT) CA *= 2;  // channel lanes: power of two covering A / V (or all threads)
@@ -550,6 +609,14 @@ hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int
   const int wh = (h.Hu + h.oh - 1) / h.oh + (h.Hu % h.oh ? 1 : 0), wwid = (h.Wu + h.ow - 1) / h.ow + (h.Wu % h.ow ? 1 : 0);
   int NS = 1;
   while (NS * 2 <= wh * wwid && CA * NS * 2 <= HT) NS *= 2;
+  *CA_out = CA, *NS_out = NS;
+}
+
+hipError_t launch_head_pool(const HeadShape &h, float *U, const float *part, int splits, const float *ba, float *Pq,
+                            int32_t *parg, hipStream_t st) {
+  const int V = h.A % 4 == 0 ? 4 : 1;
+  int CA, NS;
+  pool_lanes(h, V, &CA, &NS);
   const int G = HT / (CA * NS);
   const long long pairs = (long long)h.B * h.oh * h.ow;
   const dim3 grid((unsigned)((pairs + G - 1) / G));
@@ -580,6 +647,46 @@ hipError_t launch_head_fc(const HeadShape &h, const float *Pq, const int32_t *la
   return hipGetLastError();
 }
 
+bool head_sample_applicable(const HeadShape &h) {
+  // a sample's activation map of at most 4 KiB (measured: at 16 KiB per sample and 128 samples the
+  // three chip-wide launches are faster than 128 workgroups doing a sample each), the linear layer
+  // narrow enough that sharing its weights between samples (head_fc_wide_kernel) does not pay
+  return (long long)h.Hu * h.Wu * h.A <= 1024 && h.F <= 256 && h.Cls <= 1024;
+}
+
+hipError_t launch_head_sample(const HeadShape &h, float *U, const float *part, int splits, const float *ba,
+                              const int32_t *labels, const float *Wf, const float *bf, float *Pq, int32_t *parg, float *dz, float *loss_n, float *dU, const float *Wa,
+                              float *WaT, int R, int S, int K, hipStream_t st) {
+  const int V = h.A % 4 == 0 ? 4 : 1;
+  int CA, NS;
+  pool_lanes(h, V, &CA, &NS);
+  const unsigned nb_t = Wa ? (unsigned)(((long long)h.A * R * S * K + HT - 1) / HT) : 0;
+  const dim3 grid((unsigned)h.B + nb_t);
+  const size_t lds = (size_t)(2 * h.F + h.Cls + 8) * sizeof(float) + (h.pmax ? (size_t)h.F * sizeof(int) : 0);
+#define NF_HS(V_, P_)                                                                                              \
+  hipLaunchKernelGGL((head_sample_kernel<V_, P_>), grid, dim3(HT), lds, st, h, U, part, splits, ba, labels, Wf, bf, Pq, \
+                     parg, dz, loss_n, dU, Wa, WaT, R, S, K, CA, NS)
+  if (h.pmax) {
+    if (V == 4) NF_HS(4, true);
+    else NF_HS(1, true);
+  } else {
+    if (V == 4) NF_HS(4, false);
+    else NF_HS(1, false);
+  }
+#undef NF_HS
+  return hipGetLastError();
+}
+
+int gamma_job_plan(GammaJob &g) {
+  // feature lanes per workgroup: few, so that many batch slices share the reduction over n
+  g.fch = 8;
+  while (g.fch < 32 && g.fch * 2 <= g.F) g.fch *= 2;
+  g.nchunks = (g.F + g.fch - 1) / g.fch;
+  g.nb_w = g.Cls * g.nchunks;
+  g.nb_l = g.loss_out ? 1 : 0;
+  return g.nb_w + g.nb_l;
+}
+
 hipError_t launch_head_predict(const HeadShape &h, const float *Pq, const int32_t *labels, const float *Wf,
                                const float *bf, float *logits_out, int32_t *pred, int32_t *hit, hipStream_t st) {
   const size_t lds = (size_t)(h.F + h.Cls) * sizeof(float);
@@ -601,11 +708,10 @@ hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz,
                            const float *U, const float *dPq, float *dU, const float *Wa, float *WaT, int R, int S,
                            int K, const float *loss_n, float *loss_out, const int32_t *parg, hipStream_t st) {
   HeadBwdJobs jb;
-  // feature lanes per workgroup: few, so that many batch slices share the reduction over n
-  jb.fch = 8;
-  while (jb.fch < 32 && jb.fch * 2 <= h.F) jb.fch *= 2;
-  jb.nchunks = (h.F + jb.fch - 1) / jb.fch;
-  jb.nb_w = h.Cls * jb.nchunks;
+  GammaJob gj;
+  gj.F = h.F, gj.Cls = h.Cls, gj.loss_out = nullptr;
+  gamma_job_plan(gj);
+  jb.fch = gj.fch, jb.nchunks = gj.nchunks, jb.nb_w = gj.nb_w;
   const int V = h.A % 4 == 0 ? 4 : 1;
   const long long total = (long long)h.B * h.Hu * h.Wu * (h.A / V);
   jb.nb_u = (int)((total + HT - 1) / HT);

@@ -13,6 +13,7 @@
 // workspace and are summed in a fixed order by wgrad_reduce_kernel (deterministic).
 // Column sums of D (the bias gradient) are accumulated by the q-tile-0 workgroups from
 // the values they stage anyway.
+#include "head_gamma.h"
 #include "nf_internal.h"
 
 namespace nf {
@@ -408,6 +409,16 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(ReduceSgd r) {
     }
     b -= r.xblocks[xi];
   }
+  // the linear layer's gradient (+ update) and the batch-mean loss, when this launch carries them
+  if (r.gamma.dWf) {
+    float *redf = reinterpret_cast<float *>(red);
+    if (b < r.gamma.nb_w) {
+      gamma_block(r.gamma, b, redf, redf + 256);
+      return;
+    }
+    b -= r.gamma.nb_w;
+    if (b < r.gamma.nb_l) loss_mean_block(r.gamma.loss_n, r.gamma.B, r.gamma.loss_out, redf);
+  }
 }
 
 struct TileChoice {
@@ -499,6 +510,7 @@ hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r0, hipStream_t st) {
     r.xblocks[x] = (int)((r.xn[x] + 255) / 256);
     blocks += (unsigned)r.xblocks[x];
   }
+  if (r.gamma.dWf) blocks += (unsigned)gamma_job_plan(r.gamma);
   if (!blocks) return hipSuccess;
   hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(256), 0, st, r);
   return hipGetLastError();

@@ -102,11 +102,21 @@ WgradProblem aux_wgrad_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
   return g;
 }
 
+HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
+  HeadShape h;
+  h.B = B, h.Hu = ad.Hu, h.Wu = ad.Wu, h.A = a->A, h.oh = a->pool_oh, h.ow = a->pool_ow, h.F = ad.F,
+  h.Cls = a->n_classes, h.relu = a->relu, h.pmax = a->head_pool == 1, h.mse = a->loss_kind == 1;
+  return h;
+}
+
 struct WsLayout {
   size_t T_dZ, arg, U, Pq, parg, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
   // reduction splits of the forward-type contractions (1 = none); their partial sums alias `part`
   int ksplits_aux, ksplits_layer, ksplits_dgrad;
+  // the head's per-sample chain (pooling ... dU) runs as one launch right after its convolution;
+  // the batch-reducing rest (gamma_n's gradient, batch-mean loss) rides on the reduction launch
+  int head_fused;
 };
 
 WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B) {
@@ -155,6 +165,7 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     if (w.ksplits_aux > 1 && (size_t)w.ksplits_aux * u > pmax) pmax = (size_t)w.ksplits_aux * u;
     w.ksplits_dgrad = igemm_fwd_pick_ksplits(B * a->H_in * a->W_in, a->C_in, a->R * a->S * a->A, a->A, a->R * a->S);
     if (w.ksplits_dgrad > 1 && (size_t)w.ksplits_dgrad * emitted > pmax) pmax = (size_t)w.ksplits_dgrad * emitted;
+    w.head_fused = head_sample_applicable(head_shape(a, ad, B)) ? 1 : 0;
     w.part_b = take((size_t)w.splits_layer * d->C_out * f);
     w.part_aux = take(pa * f);
     w.part_b_aux = take((size_t)w.splits_aux * a->A * f);
@@ -297,13 +308,6 @@ int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const 
   return NF_OK;
 }
 
-HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
-  HeadShape h;
-  h.B = B, h.Hu = ad.Hu, h.Wu = ad.Wu, h.A = a->A, h.oh = a->pool_oh, h.ow = a->pool_ow, h.F = ad.F,
-  h.Cls = a->n_classes, h.relu = a->relu, h.pmax = a->head_pool == 1, h.mse = a->loss_kind == 1;
-  return h;
-}
-
 // beta_n and F_n of Eq. 2: the head's convolution (+ bias, ReLU) and its pooling; leaves U and Pq
 // (and the max-pooling selection) in the workspace
 int32_t run_aux_features(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const nf_aux_params *ap,
@@ -333,9 +337,36 @@ int32_t run_aux_features(const nf_aux_desc *a, const AuxDims &ad, int B, const f
 // loss_out == nullptr: the batch mean is left to the backward launch that follows (run_bwd)
 int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const int32_t *labels,
                     const nf_aux_params *ap, float *loss_out, void *ws, const WsLayout &w, hipStream_t st) {
+  const HeadShape hs = head_shape(a, ad, B);
+  if (w.head_fused) {
+    // small activation map: the convolution, then ONE launch for the head's whole per-sample chain
+    // (F_n, gamma_n, loss, dL/dz, dPq, dU) and the re-laid filter the data gradient will read
+    FwdProblem f;
+    std::memset((void *)&f, 0, sizeof(f));
+    f.x = y, f.w = ap->Wa, f.bias = ap->ba;
+    f.H = a->H_in, f.W = a->W_in, f.C = a->C_in, f.N = a->A, f.R = a->R, f.S = a->S, f.stride = 1, f.pad = a->pad,
+    f.Ho = ad.Hu, f.Wo = ad.Wu;
+    f.relu = a->relu ? 1 : 0;
+    f.M = B * ad.Hu * ad.Wu, f.RSC = a->R * a->S * a->C_in, f.Kg = f.RSC;
+    f.div_howo = FastDiv(ad.Hu * ad.Wu), f.div_wo = FastDiv(ad.Wu);
+    // skinny head, long reduction: split it; the per-sample launch adds the parts, bias and ReLU
+    const int ks = (w.ksplits_aux > 1 && igemm_fwd_fast_applicable(f)) ? w.ksplits_aux : 0;
+    f.ksplits = ks;
+    f.out = ks ? wsf(ws, w.part) : wsf(ws, w.U);
+    int32_t rc = enqueue_fwd(f, st);
+    if (rc) return rc;
+    const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
+    const double wa = (double)a->A * a->R * a->S * a->C_in;
+    NF_RUN(st, "head_sample", 4.0 * B * fc,
+           4.0 * ((3.0 + ks) * u + 2.0 * B * fc + (double)B * (ad.F + a->n_classes + 1.0)) + 8.0 * wa,
+           launch_head_sample(hs, wsf(ws, w.U), wsf(ws, w.part), ks, ap->ba, labels, ap->Wf, ap->bf, wsf(ws, w.Pq),
+                              reinterpret_cast<int32_t *>(wsf(ws, w.parg)), wsf(ws, w.dz), wsf(ws, w.loss_n),
+                              wsf(ws, w.dU), ap->Wa, wsf(ws, w.WaT), a->R, a->S, a->C_in, st));
+    if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
+    return NF_OK;
+  }
   int32_t rc = run_aux_features(a, ad, B, y, ap, ws, w, st);
   if (rc) return rc;
-  const HeadShape hs = head_shape(a, ad, B);
   const double fc = (double)a->n_classes * ad.F;
   NF_RUN(st, "head_fc", 4.0 * B * fc, 4.0 * (2.0 * B * fc + (double)B * (2.0 * ad.F + a->n_classes)),
          launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), wsf(ws, w.dPq), st));
@@ -358,10 +389,11 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
   // gamma_n weight gradient, back through F_n and the aux ReLU (dPq came with the forward)
   const double u = (double)B * ad.Hu * ad.Wu * a->A, fc = (double)a->n_classes * ad.F;
   const double wa = (double)a->A * a->R * a->S * a->C_in;
-  NF_RUN(st, "head_bwd", 2.0 * B * fc, 4.0 * (fc + (double)B * (2.0 * ad.F + a->n_classes) + 2.0 * u) + 8.0 * wa,
-         launch_head_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ga->Wf, ga->bf, wsf(ws, w.U), wsf(ws, w.dPq), dU, ap->Wa,
-                         wsf(ws, w.WaT), a->R, a->S, a->C_in, wsf(ws, w.loss_n), loss_out,
-                         reinterpret_cast<const int32_t *>(wsf(ws, w.parg)), st));
+  if (!w.head_fused)
+    NF_RUN(st, "head_bwd", 2.0 * B * fc, 4.0 * (fc + (double)B * (2.0 * ad.F + a->n_classes) + 2.0 * u) + 8.0 * wa,
+           launch_head_bwd(hs, wsf(ws, w.Pq), wsf(ws, w.dz), ga->Wf, ga->bf, wsf(ws, w.U), wsf(ws, w.dPq), dU, ap->Wa,
+                           wsf(ws, w.WaT), a->R, a->S, a->C_in, wsf(ws, w.loss_n), loss_out,
+                           reinterpret_cast<const int32_t *>(wsf(ws, w.parg)), st));
   // beta_n: weight + bias gradient
   {
     WgradProblem g = aux_wgrad_shape(a, ad, B);
@@ -421,12 +453,27 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
       red.job[0].v0 = vp->W, red.job[0].v1 = vp->Wp, red.job[0].vb = vp->b;
       red.job[1].v0 = va->Wa, red.job[1].vb = va->ba;
     }
-    red.nx = 2;
-    red.xw[0] = ap->Wf, red.xg[0] = ga->Wf, red.xv[0] = mom ? va->Wf : nullptr, red.xn[0] = (long long)a->n_classes * ad.F;
-    red.xw[1] = ap->bf, red.xg[1] = ga->bf, red.xv[1] = mom ? va->bf : nullptr, red.xn[1] = a->n_classes;
+    if (!w.head_fused) {
+      red.nx = 2;
+      red.xw[0] = ap->Wf, red.xg[0] = ga->Wf, red.xv[0] = mom ? va->Wf : nullptr, red.xn[0] = (long long)a->n_classes * ad.F;
+      red.xw[1] = ap->bf, red.xg[1] = ga->bf, red.xv[1] = mom ? va->bf : nullptr, red.xn[1] = a->n_classes;
+    }
     for (int j = 0; j < 2; ++j) nsgd += (double)red.job[j].P * (red.job[j].Q + 1.0);
-    nsgd += (double)red.xn[0] + (double)red.xn[1];
+    nsgd += fc + a->n_classes;
     nsgd *= mom ? 16.0 : 8.0;  // bytes beyond the gradient write
+  }
+  if (w.head_fused) {
+    // gamma_n's gradient (a sum over the batch), its update and the batch-mean loss as extra
+    // workgroups of this launch: the per-sample launch left Pq, dz and the per-sample losses
+    GammaJob &gj = red.gamma;
+    gj.B = B, gj.F = ad.F, gj.Cls = a->n_classes, gj.Pq = wsf(ws, w.Pq), gj.dz = wsf(ws, w.dz);
+    gj.dWf = ga->Wf, gj.dbf = ga->bf;
+    if (sgd) {
+      gj.Wf = ap->Wf, gj.bf = ap->bf, gj.lr = sgd->lr, gj.mu = sgd->momentum;
+      if (sgd->momentum != 0.f) gj.vWf = va->Wf, gj.vbf = va->bf;
+    }
+    gj.loss_n = wsf(ws, w.loss_n), gj.loss_out = loss_out;
+    nred += (double)B * (ad.F + a->n_classes) + fc;
   }
   NF_RUN(st, sgd ? "wgrad_reduce_sgd" : "wgrad_reduce", 0.0, 4.0 * nred + nsgd, launch_wgrad_reduce_sgd(red, st));
   return NF_OK;

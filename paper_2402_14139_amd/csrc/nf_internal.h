@@ -75,6 +75,21 @@ hipError_t launch_igemm_wgrad_fast(const WgradProblem &p, hipStream_t st, const 
 bool igemm_wgrad_small_applicable(const WgradProblem &p);
 int igemm_wgrad_small_splits(int P, int C, int B, int H);
 hipError_t launch_igemm_wgrad_small(const WgradProblem &p, hipStream_t st, const char **kernel);
+// gamma_n's gradient as a job of extra workgroups (head_gamma.h): dWf = dz^T Pq, dbf = column sums of
+// dz, optionally followed by the update of Wf / bf; plus the batch mean of the per-sample losses.
+struct GammaJob {
+  int B, F, Cls;
+  const float *Pq, *dz;
+  float *dWf, *dbf;
+  float *Wf, *bf, *vWf, *vbf;  // parameters / momentum buffers updated in place (Wf null: no update)
+  float lr, mu;
+  const float *loss_n;
+  float *loss_out;             // null: no batch-mean job
+  int fch, nchunks, nb_w, nb_l;  // filled by gamma_job_plan
+};
+// fills fch / nchunks / nb_w / nb_l; returns the number of workgroups the job needs
+int gamma_job_plan(GammaJob &g);
+
 // One weight gradient to finish: out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length
 // Q-Q0) = sum_z part[z][p][q]; ob[p] = sum_z part_b[z][p].  w*/v* (may be null): parameters and
 // momentum buffers updated in place right after, same layout as out0/out1/ob.
@@ -96,6 +111,7 @@ struct ReduceSgd {
   int xblocks[2];  // filled by the launcher
   int nx;
   float lr, mu;
+  GammaJob gamma;  // extra workgroups after the above (gamma.dWf null: none)
 };
 hipError_t launch_wgrad_reduce_sgd(const ReduceSgd &r, hipStream_t st);
 
@@ -120,6 +136,16 @@ hipError_t launch_head_predict(const HeadShape &h, const float *Pq, const int32_
                                const float *bf, float *logits_out, int32_t *pred, int32_t *hit, hipStream_t st);
 // *out = (accumulate ? *out : 0) + sum of the B hit flags
 hipError_t launch_count_hits(const int32_t *hit, int B, int32_t *out, bool accumulate, hipStream_t st);
+// Whole per-sample chain of the head in one launch, one workgroup per sample, for heads whose
+// activation map is small (head_sample_applicable): F_n, gamma_n, the loss and dL/dz, dPq and the
+// backward through F_n and the aux ReLU (dU).  Leaves Pq, dz, loss_n (and the max-pooling
+// selection) in global memory for the batch-reducing jobs (GammaJob).  Extra workgroups re-lay the
+// aux filter for the data gradient when Wa is given: WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k].
+bool head_sample_applicable(const HeadShape &h);
+hipError_t launch_head_sample(const HeadShape &h, float *U, const float *part, int splits, const float *ba,
+                              const int32_t *labels, const float *Wf, const float *bf, float *Pq, int32_t *parg,
+                              float *dz, float *loss_n, float *dU, const float *Wa, float *WaT, int R, int S, int K,
+                              hipStream_t st);
 // one launch: dWf, dbf; dU (pool + aux ReLU backward); WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa
 // is given; the batch-mean loss when loss_out is given
 hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,
