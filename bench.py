@@ -38,10 +38,20 @@ TRAFFIC_BYTES_PER_LAUNCH = {
 TRAFFIC_SOURCE = ("offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this script, scaled by a 1 GiB copy "
                   "(FETCH x 2.0, WRITE x 1.0); summary in profiles/local_step_cfg3_hbm_traffic.md; not re-measured "
                   "by this run")
-# The same counters for the HBM-bound kernels of the default workload (bytes per launch, averaged over
-# the launches of one step; same two passes, same scaling).  None: not collected for that kernel.
-HBM_COUNTER_BYTES_PER_LAUNCH = {
+# The same counters for the HBM-bound kernels of the default workload, per (kernel symbol, grid in
+# threads): (counter bytes per launch, rocprofv3 kernel-trace duration in us); same passes, same
+# scaling, durations from the --kernel-trace --stats run.  HIP-event pairs (the `hbm` figures measured
+# live below) add about 3 us to every launch, which halves the apparent rate of a 6 us copy.
+HBM_OFFLINE = {
+    "cfg3_resnet18": [
+        ("cache_copy_kernel", 1048576, 33.59e6, 6.37), ("cache_copy_kernel", 2097152, 67.15e6, 15.13),
+        ("wgrad_reduce_kernel", 235776, 17.32e6, 7.15), ("wgrad_reduce_kernel", 672512, 46.10e6, 12.17),
+        ("wgrad_reduce_kernel", 2463232, 55.98e6, 17.78), ("wgrad_reduce_kernel", 697856, 141.74e6, 25.75),
+        ("head_pool_kernel<4, false>", 65536, 8.54e6, 6.32), ("head_fc_kernel", 16384, 0.60e6, 9.65),
+        ("head_bwd_kernel<4>", 645376, 18.18e6, 7.32), ("head_sample_kernel<4, false>", 83968, 4.32e6, 12.01),
+    ],
 }
+HBM_OFFLINE_SOURCE = "profiles/local_step_cfg3_hbm_traffic.md (offline rocprofv3 passes; not re-measured by this run)"
 # kernels judged against the HBM roofline (everything that is not a contraction)
 HBM_KERNELS = ("cache_read", "cache_write", "cache_copy", "wgrad_reduce_sgd", "wgrad_reduce", "head_pool", "head_fc",
                "head_fwd", "head_bwd", "maxpool_fwd", "maxpool_bwd", "fwd_finish", "sgd", "loss_mean")
@@ -262,7 +272,6 @@ def main():
                 gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9
                 hbm.append({"kernel": r["kernel"], "launches_per_step": r["launches"] / psteps,
                             "algorithmic_bytes_per_launch": round(r["bytes"] / r["launches"]),
-                            "counter_bytes_per_launch": HBM_COUNTER_BYTES_PER_LAUNCH.get((cfg.name, r["kernel"])),
                             "avg_us": round(1e3 * r["ms"] / r["launches"], 2), "achieved_gbs": round(gbs, 1),
                             "frac_of_8tbs": round(gbs / HBM_PEAK_GBS, 4),
                             "ms_per_step": round(r["ms"] / psteps, 4)})
@@ -489,7 +498,12 @@ def main():
                    "gflop_per_step": round(flops_per_step / 1e9, 1)},
         "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
         "losses_finite": finite,
-        "roofline": roofline, "cpu_baseline": cpu, "hbm": hbm, "block_driver": block_driver, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "hbm": hbm,
+        "hbm_offline": {"source": HBM_OFFLINE_SOURCE,
+                        "rows": [{"kernel": k, "grid_threads": g, "counter_bytes_per_launch": by, "rocprof_us": us,
+                                  "gbs": round(by / us / 1e3, 1), "frac_of_8tbs": round(by / us / 1e3 / HBM_PEAK_GBS, 3)}
+                                 for k, g, by, us in HBM_OFFLINE.get(cfg.name, [])]},
+        "block_driver": block_driver, "kernels": kernels,
         "layers": per_layer, "blocks": per_block, "device": device,
     }
     print(json.dumps(out), flush=True)
