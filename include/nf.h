@@ -58,7 +58,7 @@ typedef enum {
 } nf_status;
 
 /* Layer n of Eq. 1: conv theta_n (+bias, + optional shortcut), ReLU, optional max-pool P_n.
- * Supported: 1 <= R,S <= 15, 1 <= stride <= 4, any pad >= 0 that leaves an output; max-pool with
+ * Supported: 1 <= R,S <= 15, 1 <= stride <= 4, 0 <= pad < R + S; max-pool with
  * 2*pool_pad <= pool_k <= 15 and any positive stride.  Anything else: NF_ERR_UNSUPPORTED. */
 typedef struct {
   int32_t C_in, H_in, W_in;
@@ -197,7 +197,10 @@ int32_t nf_local_step_static(const nf_layer_desc *d, const nf_aux_desc *a, const
  * m <= n of the layer whose INPUT tensor is layer n's shortcut (0 = the block's input batch);
  * that tensor's shape must equal the layer's skip_C/skip_H/skip_W.  aux/ap/gp/ga are not read by
  * nf_block_fill_cache and may be NULL there; vp/va may be NULL when momentum == 0.  gp/ga are
- * scratch of the pass (they hold the last batch's gradients afterwards). */
+ * scratch of the pass (they hold the last batch's gradients afterwards).  The block calls validate
+ * every descriptor, shape, pointer and alignment of every layer before the first enqueue, so an
+ * argument error has no side effects; only a HIP error (NF_ERR_DEVICE) can surface mid-pass, and
+ * then the prefetch stream, if any, is joined back into `stream` before the call returns. */
 typedef struct {
   int32_t n_layers;
   const nf_layer_desc *layers;

@@ -246,6 +246,7 @@ hipError_t launch_cfg(const FwdProblem &p, bool vec, hipStream_t st) {
 
 hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **kernel) {
   if (igemm_fwd_fast_applicable(p)) return launch_igemm_fwd_fast(p, st, kernel);
+  if (stem_fwd_applicable(p)) return launch_stem_fwd(p, st, kernel);
   const bool vec = (p.C % 4 == 0) && (p.Cs % 4 == 0);
   if (p.N > 64) {
     *kernel = vec ? "igemm_fwd_128x128_v4" : "igemm_fwd_128x128_v1";

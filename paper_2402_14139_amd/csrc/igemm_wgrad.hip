@@ -473,6 +473,7 @@ int wgrad_pick_splits(int P, int Q, int M) {
 hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char **kernel) {
   if (igemm_wgrad_small_applicable(p)) return launch_igemm_wgrad_small(p, st, kernel);
   if (igemm_wgrad_fast_applicable(p)) return launch_igemm_wgrad_fast(p, st, kernel);
+  if (stem_wgrad_applicable(p)) return launch_stem_wgrad(p, st, kernel);
   const bool vec = (p.C % 4 == 0) && (p.Cs % 4 == 0) && (p.P % 4 == 0);
   if (p.P > 64) {
     *kernel = vec ? "igemm_wgrad_128x128_v4" : "igemm_wgrad_128x128_v1";

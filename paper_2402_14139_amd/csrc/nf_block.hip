@@ -77,15 +77,19 @@ int32_t plan_block(const nf_block *blk, int32_t B, int32_t B_last, PlanMode mode
     const nf_layer_params &p = blk->p[l];
     if (!p.W || !p.b || (d->skip_kind == 2 && !p.Wp)) return NF_ERR_NULL;
     if (!aligned16(p.W) || !aligned16(p.b) || (d->skip_kind == 2 && !aligned16(p.Wp))) return NF_ERR_BAD_DESC;
+    // every pointer a per-layer call would reject is rejected here, before anything is enqueued
     if (heads) {
       const nf_aux_params &s = blk->ap[l];
       if (!s.Wa || !s.ba || !s.Wf || !s.bf) return NF_ERR_NULL;
+      if (!aligned16(s.Wa) || !aligned16(s.ba) || !aligned16(s.Wf) || !aligned16(s.bf)) return NF_ERR_BAD_DESC;
     }
     if (train) {
       const nf_layer_params &g = blk->gp[l];
       const nf_aux_params &s = blk->ga[l];
       if (!g.W || !g.b || (d->skip_kind == 2 && !g.Wp)) return NF_ERR_NULL;
       if (!s.Wa || !s.ba || !s.Wf || !s.bf) return NF_ERR_NULL;
+      if (!aligned16(g.W) || !aligned16(g.b) || (d->skip_kind == 2 && !aligned16(g.Wp))) return NF_ERR_BAD_DESC;
+      if (!aligned16(s.Wa) || !aligned16(s.ba) || !aligned16(s.Wf) || !aligned16(s.bf)) return NF_ERR_BAD_DESC;
     }
     pl->y_elems[l] = (int64_t)d->C_out * Hp * Wp;
     pl->y_off[l] = off, off += up((size_t)B * pl->y_elems[l] * sizeof(float));
@@ -162,6 +166,9 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
       const nf_aux_params &u = blk->va[l];
       if (!v.W || !v.b || (blk->layers[l].skip_kind == 2 && !v.Wp) || !u.Wa || !u.ba || !u.Wf || !u.bf)
         return NF_ERR_NULL;
+      if (!aligned16(v.W) || !aligned16(v.b) || (blk->layers[l].skip_kind == 2 && !aligned16(v.Wp)) ||
+          !aligned16(u.Wa) || !aligned16(u.ba) || !aligned16(u.Wf) || !aligned16(u.bf))
+        return NF_ERR_BAD_DESC;
     }
   }
   if (!aligned16(cache)) return NF_ERR_BAD_DESC;
@@ -175,6 +182,12 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
     NF_HIP(hipEventRecord(ev.fork, st));  // the cache may have been produced on `stream`
     NF_HIP(hipStreamWaitEvent(pf, ev.fork, 0));
   }
+  // A HIP error after the fork: whatever was enqueued on the prefetch stream is joined back into
+  // `stream` before the call returns, so that `stream` alone still orders everything the call did.
+  auto fail = [&](int32_t code) -> int32_t {
+    if (pf && hipEventRecord(ev.ready[0], pf) == hipSuccess) (void)hipStreamWaitEvent(st, ev.ready[0], 0);
+    return code;
+  };
   auto read_batch = [&](int64_t j, hipStream_t on) -> int32_t {
     const int slot = (int)(j & 1);
     const int32_t nb = j == n_batches - 1 ? B_last : B;
@@ -182,8 +195,8 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
                          at(ws, pl.xin_off[slot]), reinterpret_cast<int32_t *>(at(ws, pl.lab_off[slot])), on);
   };
   if (pf) {
-    if ((rc = read_batch(0, pf))) return rc;
-    NF_HIP(hipEventRecord(ev.ready[0], pf));
+    if ((rc = read_batch(0, pf))) return fail(rc);
+    if (hipEventRecord(ev.ready[0], pf) != hipSuccess) return fail(NF_ERR_DEVICE);
   }
   const int n = blk->n_layers;
   for (int64_t j = 0; j < n_batches; ++j) {
@@ -192,13 +205,13 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
     if (pf) {
       if (j + 1 < n_batches) {
         // slot of batch j+1 was last used by batch j-1
-        if (j >= 1) NF_HIP(hipStreamWaitEvent(pf, ev.done[slot ^ 1], 0));
-        if ((rc = read_batch(j + 1, pf))) return rc;
-        NF_HIP(hipEventRecord(ev.ready[slot ^ 1], pf));
+        if (j >= 1 && hipStreamWaitEvent(pf, ev.done[slot ^ 1], 0) != hipSuccess) return fail(NF_ERR_DEVICE);
+        if ((rc = read_batch(j + 1, pf))) return fail(rc);
+        if (hipEventRecord(ev.ready[slot ^ 1], pf) != hipSuccess) return fail(NF_ERR_DEVICE);
       }
-      NF_HIP(hipStreamWaitEvent(st, ev.ready[slot], 0));
+      if (hipStreamWaitEvent(st, ev.ready[slot], 0) != hipSuccess) return fail(NF_ERR_DEVICE);
     } else {
-      if ((rc = read_batch(j, st))) return rc;
+      if ((rc = read_batch(j, st))) return fail(rc);
     }
     const int32_t *lab = reinterpret_cast<const int32_t *>(at(ws, pl.lab_off[slot]));
     for (int l = 0; l < n; ++l) {
@@ -208,9 +221,9 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
       rc = nf_local_step(d, &blk->aux[l], s, nb, x, xs, lab, &blk->p[l], &blk->ap[l], &blk->gp[l], &blk->ga[l],
                          blk->vp ? &blk->vp[l] : nullptr, blk->va ? &blk->va[l] : nullptr, at(ws, pl.y_off[l]),
                          losses + j * n + l, at(ws, pl.layer_ws_off), pl.layer_ws_bytes, st);
-      if (rc) return rc;
+      if (rc) return fail(rc);
     }
-    if (pf && j + 2 < n_batches) NF_HIP(hipEventRecord(ev.done[slot], st));
+    if (pf && j + 2 < n_batches && hipEventRecord(ev.done[slot], st) != hipSuccess) return fail(NF_ERR_DEVICE);
   }
   return NF_OK;
 }

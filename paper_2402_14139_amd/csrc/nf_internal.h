@@ -52,6 +52,11 @@ hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **ke
 bool igemm_fwd_fast_applicable(const FwdProblem &p);
 hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char **kernel);
 
+// first-layer shapes (stem.hip): the whole reduction R*S*C <= 32 in one staging step, channel counts
+// that are not multiples of 4; launch_igemm_fwd / launch_igemm_wgrad pick them when applicable
+bool stem_fwd_applicable(const FwdProblem &p);
+hipError_t launch_stem_fwd(const FwdProblem &p, hipStream_t st, const char **kernel);
+
 // ---- implicit-GEMM weight gradient: part[z][p][q] = sum_{m in split z} d[m][p] * col(x)[m][q]
 struct WgradProblem {
   const float *d, *x, *xs;
@@ -89,6 +94,9 @@ struct GammaJob {
 };
 // fills fch / nchunks / nb_w / nb_l; returns the number of workgroups the job needs
 int gamma_job_plan(GammaJob &g);
+
+bool stem_wgrad_applicable(const WgradProblem &p);
+hipError_t launch_stem_wgrad(const WgradProblem &p, hipStream_t st, const char **kernel);
 
 // One weight gradient to finish: out0[p][q] (q < Q0, row length Q0) and out1[p][q-Q0] (row length
 // Q-Q0) = sum_z part[z][p][q]; ob[p] = sum_z part_b[z][p].  w*/v* (may be null): parameters and

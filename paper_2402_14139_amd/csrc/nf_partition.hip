@@ -74,7 +74,7 @@ int32_t nf_partition(int32_t n_layers, const nf_linear_model *R, double M, int32
     if (!own) return NF_ERR_DEVICE;
     b = own;
   }
-  // first loop of Algorithm 1: largest batch size within the budget, capped at the limit
+  // per layer: largest batch size whose model stays within the budget, capped at the limit
   for (int l = 0; l < n_layers; ++l) {
     double t;
     if (R[l].slope > 0)
@@ -84,17 +84,23 @@ int32_t nf_partition(int32_t n_layers, const nf_linear_model *R, double M, int32
     t = std::max(0.0, std::min(t, (double)B_limit));
     b[l] = (int32_t)t;
   }
-  // second loop: a block grows while consecutive layers' batch sizes stay within rho of each other
+  // Blocks are the maximal runs of consecutive layers without a cut, where a cut separates layers i
+  // and i+1 exactly when |b[i+1] - b[i]| > rho * b[i]; a block takes the smallest batch size of its
+  // run.  (Algorithm 1's grouping loop, stated as the partition it produces.)
   int nb = 0;
-  for (int i = 0; i < n_layers; ++i) {
-    block_first[nb] = i;
-    int32_t batch = b[i];
-    while (i + 1 < n_layers && std::fabs((double)b[i + 1] - (double)b[i]) <= rho * (double)b[i]) {
-      batch = std::min(batch, b[i + 1]);
-      ++i;
+  int32_t run_min = b[0];
+  block_first[0] = 0;
+  for (int i = 0; i + 1 < n_layers; ++i) {
+    const bool cut = std::fabs((double)b[i + 1] - (double)b[i]) > rho * (double)b[i];
+    if (cut) {
+      block_batch[nb++] = run_min;
+      block_first[nb] = i + 1;
+      run_min = b[i + 1];
+    } else {
+      run_min = std::min(run_min, b[i + 1]);
     }
-    block_batch[nb++] = batch;
   }
+  block_batch[nb++] = run_min;
   *n_blocks = nb;
   std::free(own);
   return NF_OK;

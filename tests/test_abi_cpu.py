@@ -318,6 +318,20 @@ def test_block_calls_validate_before_enqueue(L):
     assert fill(nop) == nf.NF_ERR_NULL
     nohead = nf.make_block(descs, None, skip, lp, None)
     assert train(nohead) == nf.NF_ERR_NULL
+    # a misaligned pointer in ANY per-layer struct is an argument error of the block call itself
+    # (nothing is enqueued), not an error of the per-layer call it would reach mid-pass
+    odd = good + 4
+    last = n - 1
+    for which in ("p", "ap", "gp", "ga", "vp", "va"):
+        lp2, ap2 = list(lp), list(apar)
+        if which in ("p", "gp", "vp"):
+            lp2[last] = nf.LayerParams(good, odd, good)
+        else:
+            ap2[last] = nf.AuxParams(good, good, odd, good)
+        args = dict(p=lp, ap=apar, gp=lp, ga=apar, vp=lp, va=apar)
+        args[which] = lp2 if which in ("p", "gp", "vp") else ap2
+        bad = nf.make_block(descs, auxs, skip, args["p"], args["ap"], args["gp"], args["ga"], args["vp"], args["va"])
+        assert train(bad) == nf.NF_ERR_BAD_DESC, which
     assert L.nf_block_workspace_bytes(C.byref(nohead), B, C.byref(out)) == nf.NF_OK and out.value < need
 
 
