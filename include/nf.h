@@ -292,8 +292,9 @@ int32_t nf_partition(int32_t n_layers, const nf_linear_model *R, double M, int32
  * HIP-event pair on the caller's stream.  nf_prof_end waits for those events (the only call
  * that blocks the host), and returns one record per kernel: launches, summed duration (ms),
  * summed algorithmic FLOPs and bytes.  Records are sorted by duration, at most `cap` are
- * written, *n receives the number of distinct kernels.  Process-wide, not thread-safe, creates
- * HIP events: keep it out of production loops. */
+ * written, *n receives the number of distinct kernels.  Process-wide state (one recording at a time;
+ * the record list is guarded by a mutex so that launches from several host threads may be recorded),
+ * creates HIP events: keep it out of production loops. */
 typedef struct {
   char kernel[48];
   int64_t launches;

@@ -204,6 +204,7 @@ struct ProfEvent {
 struct ProfState {
   bool on = false;
   std::vector<ProfEvent> ev;
+  std::mutex mu;  // guards ev: launches from several host threads may record while profiling is on
 };
 ProfState g_prof;
 
@@ -217,7 +218,10 @@ struct ProfScope {
     }
   }
   void done(const char *name, double flops, double bytes) {
-    if (on && hipEventRecord(b, st) == hipSuccess) g_prof.ev.push_back({name, a, b, flops, bytes});
+    if (on && hipEventRecord(b, st) == hipSuccess) {
+      std::lock_guard<std::mutex> lk(g_prof.mu);
+      g_prof.ev.push_back({name, a, b, flops, bytes});
+    }
   }
 };
 
@@ -816,6 +820,7 @@ int32_t nf_device_info(int32_t *compute_units, int32_t *clock_khz) {
 }
 
 int32_t nf_prof_begin(void) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
   for (auto &e : g_prof.ev) {
     (void)hipEventDestroy(e.a);
     (void)hipEventDestroy(e.b);
@@ -828,6 +833,7 @@ int32_t nf_prof_begin(void) {
 int32_t nf_prof_end(nf_prof_record *out, int32_t cap, int32_t *n) {
   g_prof.on = false;
   if (!n || (cap > 0 && !out)) return NF_ERR_NULL;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
   std::vector<nf_prof_record> agg;
   int32_t rc = NF_OK;
   for (auto &e : g_prof.ev) {
