@@ -54,7 +54,7 @@ HBM_OFFLINE = {
 HBM_OFFLINE_SOURCE = "profiles/local_step_cfg3_hbm_traffic.md (offline rocprofv3 passes; not re-measured by this run)"
 # kernels judged against the HBM roofline (everything that is not a contraction)
 HBM_KERNELS = ("cache_read", "cache_write", "cache_copy", "wgrad_reduce_sgd", "wgrad_reduce", "head_pool", "head_fc",
-               "head_fwd", "head_bwd", "maxpool_fwd", "maxpool_bwd", "fwd_finish", "sgd", "loss_mean")
+               "head_sample", "head_bwd", "maxpool_fwd", "maxpool_bwd", "fwd_finish", "sgd", "loss_mean")
 
 
 def layer_flops(ls, B, n_classes):
@@ -333,6 +333,55 @@ def main():
         del src, dst
     log(f"[device] {device}")
 
+    # ---- cache streams at the step's own sizes: 20 launches back to back, captured in a HIP graph
+    # and replayed between ONE event pair (the per-launch event pairs above add ~3 us to every
+    # launch, and 20 eager launches of a 6 us copy are bound by the host's call rate): the shuffled
+    # row gather of every block's batch, and the write of its output
+    cache_stream = []
+    if not args.no_prof:
+        reps = 20
+
+        def timed_graph(fn):
+            try:
+                gph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gph):
+                    for r in range(reps):
+                        fn(r)
+                torch.cuda.synchronize()
+                gph.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                gph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) * 1e3 / reps
+            except Exception as exc:  # noqa: BLE001
+                log(f"[cache] HIP-graph capture not available: {exc}")
+                torch.cuda.synchronize()
+                return None
+
+        for k in range(nblk):
+            B = cfg.blocks[k].batch
+            nb = N // B
+            sl = [perms[k][(r % nb) * B:(r % nb + 1) * B] for r in range(reps)]
+            us = timed_graph(lambda r: nf.nf_cache_read(caches[k], clabels[k], N, se[k], 0, sl[r], B, xin[k], lin[k]))
+            by = 8.0 * se[k] * B + 16.0 * B
+            if us:
+                cache_stream.append({"op": "cache_read", "block": k, "B": B, "bytes_per_launch": by, "us": round(us, 2),
+                                     "gbs": round(by / us / 1e3, 1), "frac_of_8tbs": round(by / us / 1e3 / HBM_PEAK_GBS, 4)})
+            if k + 1 < nblk:
+                y = layers[cfg.blocks[k].layers[-1]].y
+                us = timed_graph(lambda r: nf.nf_cache_write(wcaches[k + 1], wlabels[k + 1], N, se[k + 1], (r % nb) * B, B,
+                                                             y, lin[k]))
+                by = 8.0 * se[k + 1] * B + 8.0 * B
+                if us:
+                    cache_stream.append({"op": "cache_write", "block": k, "B": B, "bytes_per_launch": by,
+                                         "us": round(us, 2), "gbs": round(by / us / 1e3, 1),
+                                         "frac_of_8tbs": round(by / us / 1e3 / HBM_PEAK_GBS, 4)})
+        for c in cache_stream:
+            log(f"[cache] {c['op']:<11} block {c['block']} B={c['B']:<4d} {c['bytes_per_launch'] / 1e6:7.1f} MB "
+                f"{c['us']:7.2f} us {c['gbs']:8.1f} GB/s ({100 * c['frac_of_8tbs']:.1f} % of 8 TB/s)")
+
     # ---- the same work through the block-level calls (Worker loop inside the library) ----------
     # per block: nf_block_train_epoch over `steps` shuffled batches of its cache, without and with
     # the prefetch stream (read of batch j+1 overlapping the training of batch j); then the
@@ -498,7 +547,7 @@ def main():
                    "gflop_per_step": round(flops_per_step / 1e9, 1)},
         "tflops": round(tflops, 2), "mfma_f32_peak_frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4),
         "losses_finite": finite,
-        "roofline": roofline, "cpu_baseline": cpu, "hbm": hbm,
+        "roofline": roofline, "cpu_baseline": cpu, "hbm": hbm, "cache_stream": cache_stream,
         "hbm_offline": {"source": HBM_OFFLINE_SOURCE,
                         "rows": [{"kernel": k, "grid_threads": g, "counter_bytes_per_launch": by, "rocprof_us": us,
                                   "gbs": round(by / us / 1e3, 1), "frac_of_8tbs": round(by / us / 1e3 / HBM_PEAK_GBS, 3)}
