@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--lr", type=float, default=None, help="override the configuration's learning rate")
     ap.add_argument("--head-pool", choices=["avg", "max"], default="avg", help="the heads' down-sampling F_n")
     ap.add_argument("--loss", choices=["ce", "mse"], default="ce", help="the local loss of Eq. 3")
+    ap.add_argument("--contraction", choices=["f32", "bf16x6"], default="f32",
+                    help="how the wide contractions run: fp32 matrix-core instructions (the default), or "
+                         "bf16 matrix-core instructions on three-way split fp32 operands (same accuracy)")
     ap.add_argument("--trace-loss", action="store_true", help="print every layer's loss after each step (syncs)")
     ap.add_argument("--traffic-calib", action="store_true",
                     help="only run 5 plain copies of 1 GiB (nf_cache_read, contiguous rows): the known-size kernel "
@@ -100,6 +103,7 @@ def main():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
     nf.lib()
+    nf.nf_contraction(nf.NF_CONTRACT_BF16X6 if args.contraction == "bf16x6" else nf.NF_CONTRACT_F32)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.traffic_calib:

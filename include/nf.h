@@ -26,9 +26,9 @@
  * ---- Ownership, streams, errors -----------------------------------------------------------
  *   The caller owns every buffer, including the workspace `ws` (size from
  *   nf_workspace_bytes, 256-byte aligned).  The library allocates nothing and keeps no
- *   state between calls (three documented exceptions: the static scratch array of
- *   nf_local_step_static, the event pool of the prefetch mode of nf_block_train_epoch, and the
- *   measurement aid nf_prof_begin/end).  `stream` is a hipStream_t passed as void* (NULL = default
+ *   state between calls (four documented exceptions: the static scratch array of
+ *   nf_local_step_static, the event pool of the prefetch mode of nf_block_train_epoch, the
+ *   process-wide contraction mode of nf_contraction, and the measurement aid nf_prof_begin/end).  `stream` is a hipStream_t passed as void* (NULL = default
  *   stream); every call only enqueues work on it and never synchronises the host.
  *   Every device pointer must be 16-byte aligned.
  *   Every call returns NF_OK (0) or a negative nf_status.  Arguments are validated before
@@ -100,6 +100,20 @@ typedef struct {
 } nf_aux_params;
 
 const char *nf_strerror(int32_t status);
+
+/* How the wide contractions (the convolution of Eq. 1 and its weight gradient in Algorithm 2, for
+ * layers with more than 128 filters) are carried out.  Operands, results and accumulation are fp32
+ * in both modes.
+ *   NF_CONTRACT_F32     (default) fp32 matrix-core instructions (v_mfma_f32_32x32x2_f32).
+ *   NF_CONTRACT_BF16X6  each fp32 operand element is cut into three bfloat16 pieces that sum to it
+ *                       exactly; six of the nine piece products (all but the three below 2^-23 of
+ *                       the product) are accumulated in fp32 by bf16 matrix-core instructions.
+ *                       Same error bound per multiply-add as an fp32 multiply followed by an fp32
+ *                       add; an operand element that is +-inf gives NaN instead of +-inf.
+ * Process-wide (read when a call enqueues its kernels); returns the previous mode, or
+ * NF_ERR_BAD_DESC for an unknown mode.  mode = -1 only queries. */
+enum { NF_CONTRACT_F32 = 0, NF_CONTRACT_BF16X6 = 1 };
+int32_t nf_contraction(int32_t mode);
 
 /* Emitted sizes: conv output (Ho,Wo) and post-pool (Hp,Wp).  Any out pointer may be NULL. */
 int32_t nf_layer_out_dims(const nf_layer_desc *d, int32_t *Ho, int32_t *Wo, int32_t *Hp, int32_t *Wp);

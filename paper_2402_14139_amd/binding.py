@@ -18,13 +18,14 @@ NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE
     -1, -2, -3, -4, -5, -6)
 NF_ERR_SCRATCH_LIMIT = -7
 NF_STATIC_SCRATCH_BYTES = 128 << 20
+NF_CONTRACT_F32, NF_CONTRACT_BF16X6 = 0, 1
 
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
            "nf_block_train_epoch", "nf_block_fill_cache", "nf_layer_step_bytes", "nf_fit_linear",
            "nf_profile_layer", "nf_partition", "nf_aux_predict", "nf_block_evaluate", "nf_select_exit",
-           "nf_device_info", "nf_local_step_static")
+           "nf_device_info", "nf_local_step_static", "nf_contraction")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
 NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
@@ -136,6 +137,7 @@ def lib():
                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nf_select_exit.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         L.nf_device_info.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.nf_contraction.argtypes = [C.c_int32]
         L.nf_layer_step_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_int32,
                                           C.POINTER(C.c_size_t)]
         L.nf_fit_linear.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(LinearModel)]
@@ -382,6 +384,15 @@ def nf_select_exit(n_correct, n_params) -> int:
     _check(lib().nf_select_exit(n, (C.c_int64 * n)(*n_correct), (C.c_int64 * n)(*n_params), C.byref(out)),
            "nf_select_exit")
     return int(out.value)
+
+
+def nf_contraction(mode: int = -1) -> int:
+    """Sets the process-wide contraction mode (NF_CONTRACT_F32 / NF_CONTRACT_BF16X6) and returns the
+    previous one; mode = -1 only queries."""
+    rc = int(lib().nf_contraction(int(mode)))
+    if rc < 0:
+        _check(rc, "nf_contraction")
+    return rc
 
 
 def nf_device_info():

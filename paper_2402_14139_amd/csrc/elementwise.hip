@@ -95,7 +95,7 @@ __global__ __launch_bounds__(ET) void maxpool_bwd_kernel(const float *__restrict
         const float yv[4] = {y4.x, y4.y, y4.z, y4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          acc[e] += ((int)((a4 >> (8 * e)) & 0xffu) == local) & (yv[e] > 0.f) ? dv[e] : 0.f;
+          acc[e] += (((int)((a4 >> (8 * e)) & 0xffu) == local) & (yv[e] > 0.f)) ? dv[e] : 0.f;
       } else {
 #pragma unroll
         for (int e = 0; e < V; ++e)

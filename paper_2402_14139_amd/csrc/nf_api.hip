@@ -2,6 +2,7 @@
 // order in which the kernels of one local training step are enqueued (body of Algorithm 2,
 // NeuroFlux, arXiv 2402.14139).  No device work is enqueued before validation has passed.
 #include <algorithm>
+#include <atomic>
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
@@ -15,6 +16,9 @@
 static __device__ __align__(256) unsigned char scratch[NF_STATIC_SCRATCH_BYTES];
 
 namespace nf {
+
+std::atomic<int> g_contraction{NF_CONTRACT_F32};
+int contraction_mode() { return g_contraction.load(std::memory_order_relaxed); }
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -588,6 +592,12 @@ int32_t local_step_impl(const nf_layer_desc *d, const nf_aux_desc *a, const nf_s
 using namespace nf;
 
 extern "C" {
+
+int32_t nf_contraction(int32_t mode) {
+  if (mode == -1) return nf::g_contraction.load();
+  if (mode != NF_CONTRACT_F32 && mode != NF_CONTRACT_BF16X6) return NF_ERR_BAD_DESC;
+  return nf::g_contraction.exchange(mode);
+}
 
 const char *nf_strerror(int32_t s) {
   switch (s) {

@@ -52,6 +52,13 @@ hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **ke
 bool igemm_fwd_fast_applicable(const FwdProblem &p);
 hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char **kernel);
 
+// current contraction mode (nf_contraction): NF_CONTRACT_F32 or NF_CONTRACT_BF16X6
+int contraction_mode();
+// fp32 contraction on the bf16 matrix cores through three-way split operands (igemm_fwd_split.hip);
+// launch_igemm_fwd_fast hands over to it in NF_CONTRACT_BF16X6 mode when applicable
+bool igemm_fwd_split_applicable(const FwdProblem &p);
+hipError_t launch_igemm_fwd_split(const FwdProblem &p, hipStream_t st, const char **kernel);
+
 // first-layer shapes (stem.hip): the whole reduction R*S*C <= 32 in one staging step, channel counts
 // that are not multiples of 4; launch_igemm_fwd / launch_igemm_wgrad pick them when applicable
 bool stem_fwd_applicable(const FwdProblem &p);

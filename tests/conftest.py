@@ -17,3 +17,18 @@ def oracle():
     import oracle as _o
     _o.lib()
     return _o
+
+
+@pytest.fixture(scope="session", autouse=True)
+def contraction_mode():
+    """NF_CONTRACTION=bf16x6 runs the whole suite with the wide contractions on the bf16 matrix
+    cores (three-way split operands); unset or f32: the default fp32 matrix-core instructions."""
+    want = os.environ.get("NF_CONTRACTION", "")
+    if want in ("", "f32"):
+        yield
+        return
+    assert want == "bf16x6", f"NF_CONTRACTION={want!r}: expected f32 or bf16x6"
+    from paper_2402_14139_amd import binding as B
+    prev = B.nf_contraction(B.NF_CONTRACT_BF16X6)
+    yield
+    B.nf_contraction(prev)
