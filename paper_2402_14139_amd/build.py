@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnf.so")
-SOURCES = ["nf_api.hip", "nf_block.hip", "nf_partition.hip", "igemm_fwd.hip", "igemm_fwd_fast.hip", "igemm_fwd_split.hip", "igemm_wgrad.hip", "igemm_wgrad_fast.hip", "igemm_wgrad_small.hip", "head.hip", "elementwise.hip", "stem.hip"]
+SOURCES = ["nf_api.hip", "nf_block.hip", "nf_partition.hip", "igemm_fwd.hip", "igemm_fwd_fast.hip", "igemm_fwd_split.hip", "igemm_wgrad.hip", "igemm_wgrad_fast.hip", "igemm_wgrad_split.hip", "igemm_wgrad_small.hip", "head.hip", "elementwise.hip", "stem.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-parameter"]

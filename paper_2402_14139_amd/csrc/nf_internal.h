@@ -82,6 +82,10 @@ hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char 
 // software-pipelined buffer-load variant (igemm_wgrad_fast.hip); launch_igemm_wgrad picks it when applicable
 bool igemm_wgrad_fast_applicable(const WgradProblem &p);
 hipError_t launch_igemm_wgrad_fast(const WgradProblem &p, hipStream_t st, const char **kernel);
+// fp32 weight gradient on the bf16 matrix cores through three-way split operands
+// (igemm_wgrad_split.hip); launch_igemm_wgrad_fast hands over to it in NF_CONTRACT_BF16X6 mode
+bool igemm_wgrad_split_applicable(const WgradProblem &p);
+hipError_t launch_igemm_wgrad_split(const WgradProblem &p, hipStream_t st, const char **kernel);
 // 3x3 / stride 1 / pad 1 with at most 32 output channels (igemm_wgrad_small.hip): 4x4x1 MFMA with a
 // sliding register window; `splits` are ranges of image rows there (any count is valid)
 bool igemm_wgrad_small_applicable(const WgradProblem &p);
