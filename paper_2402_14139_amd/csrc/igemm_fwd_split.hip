@@ -81,8 +81,8 @@ __device__ inline floatx16 mfma_bf16(uint4 a, uint4 b, floatx16 c) {
 // 512 threads = two groups of four waves, one wave of each group per SIMD.  The groups take the
 // reduction steps alternately (group 0 the even ones), each with its own accumulators (added once
 // at the end, group 0 + group 1) and its own LDS buffer.  Every wave runs the same loop -- the 48
-// MFMAs of a step; barrier; split the operands of its next step into the buffer and start the loads
-// of the step after; barrier -- but group 1 runs it one barrier late, so that between two barriers
+// MFMAs of a step, with the loads of its next step issued among them; barrier; split the operands
+// of that next step into the buffer; barrier -- but group 1 runs it one barrier late, so that between two barriers
 // one group is in its MFMAs while the other splits.  A wave issues in order and an MFMA that finds
 // the matrix pipe busy holds everything behind it: the vector-ALU work of the split has to come
 // from another wave of the SIMD to overlap with the MFMAs.
@@ -165,8 +165,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // Branch-free gather of step kb (see igemm_fwd_fast.hip): steps past the end, the padding of the
   // reduction axis, taps outside the image and rows past M or N all become an out-of-range offset
   // (top bit set), for which the hardware returns zeros.
-  auto gload = [&](int kb) {
-    int offa[PA][2], offb[PB][2];
+  int offa[PA][2], offb[PB][2];
+  bool is_proj = false;  // uniform: the step reads the shortcut tensor and its 1x1 filter
+  auto gaddr = [&](int kb) {
     // half hf of the chunk: 4 consecutive kg inside one filter tap
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
@@ -193,7 +194,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int i = 0; i < PB; ++i) offb[i][hf] = (bbase[i] + kg * 4) | oob_in | (bbase[i] & OOB);
     }
-    bool is_proj = false;  // uniform: the step reads the shortcut tensor and its 1x1 filter
     if constexpr (PROJ) {
       is_proj = kb >= q.nkb_conv;
 #pragma unroll
@@ -206,17 +206,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int i = 0; i < PB; ++i) offb[i][hf] = is_proj ? ((pbase[i] + cp * 4) | oob_p | (pbase[i] & OOB)) : offb[i][hf];
       }
     }
+  };
+  // load i of the step whose offsets gaddr computed: chunk i / 2 (the A tile's first), half i % 2
+  constexpr int NLD = 2 * (PA + PB);
+  auto gissue = [&](int i) {
+    const int c = i >> 1, hf = i & 1;
     if (PROJ && is_proj) {
-#pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i][0] = bload(rxs, offa[i][0]), ra[i][1] = bload(rxs, offa[i][1]);
-#pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i][0] = bload(rwp, offb[i][0]), rb[i][1] = bload(rwp, offb[i][1]);
-      return;
+      if (c < PA) ra[c][hf] = bload(rxs, offa[c][hf]);
+      else rb[c - PA][hf] = bload(rwp, offb[c - PA][hf]);
+    } else {
+      if (c < PA) ra[c][hf] = bload(rx, offa[c][hf]);
+      else rb[c - PA][hf] = bload(rw, offb[c - PA][hf]);
     }
+  };
+  auto gload = [&](int kb) {
+    gaddr(kb);
 #pragma unroll
-    for (int i = 0; i < PA; ++i) ra[i][0] = bload(rx, offa[i][0]), ra[i][1] = bload(rx, offa[i][1]);
-#pragma unroll
-    for (int i = 0; i < PB; ++i) rb[i][0] = bload(rw, offb[i][0]), rb[i][1] = bload(rw, offb[i][1]);
+    for (int i = 0; i < NLD; ++i) gissue(i);
   };
 
   // split the staged chunks into their pieces and write them to LDS buffer `buf`
@@ -269,8 +275,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   // one reduction step out of the group's buffer: the fragments of the second slab are read under
   // the MFMAs of the first (one read per MFMA, nothing crosses: left alone, the scheduler moves
-  // every read next to its first use to save registers)
-  auto compute = [&]() {
+  // every read next to its first use to save registers).  The loads of the group's next step (its
+  // registers are free since the last split; offsets computed one step ago) are issued among the
+  // first MFMAs, and the offsets of the step after (`kb_after`) are computed among the last: this
+  // phase is bound by the matrix pipe and has issue slots to spare, the staging phase has none.
+  auto compute = [&](int kb_after) {
 #pragma unroll
     for (int r = 0; r < NR; ++r) lfrag1(0, 0, r);
     __builtin_amdgcn_sched_barrier(0);
@@ -278,8 +287,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i < NM; ++i) {
       if (i < NR) lfrag1(1, 1, i);
       mma1(0, i);
+      if (i < NLD) gissue(i);
       __builtin_amdgcn_sched_barrier(0);
     }
+    gaddr(kb_after);
 #pragma unroll
     for (int i = 0; i < NM; ++i) mma1(1, i);
   };
@@ -288,21 +299,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nper = (kb_end - kb0 + 1) >> 1;  // steps per group
   int kb = kb0 + grp;
   gload(kb);
-  if (grp == 0) {
-    stage();
-    gload(kb += 2);
-  }
+  if (grp == 0) stage();
   __syncthreads();
   if (grp == 1) {
     stage();
-    gload(kb += 2);
     __syncthreads();
   }
+  gaddr(kb += 2);
   for (int i = 0; i < nper; ++i) {
-    compute();
+    compute(kb += 2);
     __syncthreads();
     stage();
-    gload(kb += 2);
     __syncthreads();
   }
   if (grp == 0) __syncthreads();  // group 1 started one barrier late
@@ -397,7 +404,7 @@ hipError_t launch_cfg(const FwdProblem &p, SplitAux q, hipStream_t st) {
 
 // same operand limits as the fp32 buffer-load kernel (the caller has checked igemm_fwd_fast_applicable);
 // the wide tile only: many filters and a reduction of more than five steps
-bool igemm_fwd_split_applicable(const FwdProblem &p) { return p.N > 128 && p.Kg > 160; }
+bool igemm_fwd_split_applicable(const FwdProblem &p) { return p.N >= 128 && p.Kg > 160; }
 
 hipError_t launch_igemm_fwd_split(const FwdProblem &p, hipStream_t st, const char **kernel) {
   SplitAux q;

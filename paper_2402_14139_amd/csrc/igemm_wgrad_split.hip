@@ -154,29 +154,34 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   // Branch-free gather of the group's k-th step: "no data here" (row past the split, tap outside
   // the image, column past P or Q) is an out-of-range offset that the hardware answers with zeros.
-  auto gload = [&](int k) {
+  int off[8];
+  auto gaddr = [&](int k) {
     const int mb = m_begin + (2 * k + grp) * BKM + mg * 8;
     if (!is_x) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int m = mb + i;
         const bool ok = (m < m_end) & (dcol_off != OOB);
-        rd[i] = bload(rsd, (m * p.P * 4 + dcol_off) | (ok ? 0 : OOB));
+        off[i] = (m * p.P * 4 + dcol_off) | (ok ? 0 : OOB);
       }
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int4 e = Rt[grp][k & 3][mg * 8 + i];
-        int off;
         if (PROJ && tile_proj) {
-          off = (e.w + qc * 4) | ((is_proj & (e.y > -(1 << 19))) ? 0 : OOB);
+          off[i] = (e.w + qc * 4) | ((is_proj & (e.y > -(1 << 19))) ? 0 : OOB);
         } else {
           const bool ok = is_tap & ((unsigned)(e.y + qr) < (unsigned)p.H) & ((unsigned)(e.z + qs) < (unsigned)p.W);
-          off = (e.x + xtap_off) | (ok ? 0 : OOB);
+          off[i] = (e.x + xtap_off) | (ok ? 0 : OOB);
         }
-        rd[i] = bload(rsx, off);
       }
     }
+  };
+  auto gissue = [&](int i) { rd[i] = bload(is_x ? rsx : rsd, off[i]); };
+  auto gload = [&](int k) {
+    gaddr(k);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gissue(i);
   };
 
   // split the task's 32 values and write them, transposed, into the group's buffer: per column
@@ -229,8 +234,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     acc[a][b] = mfma_bf16(af[slot][PCA[pr]][a], bfr[slot][PCB[pr]][b], acc[a][b]);
   };
   // one reduction step out of the group's buffer: the fragments of the second slab are read under
-  // the MFMAs of the first (one read per MFMA, nothing crosses)
-  auto compute = [&]() {
+  // the MFMAs of the first (one read per MFMA, nothing crosses).  The loads of the group's next step
+  // (its registers are free since the last split; offsets computed one step ago) are issued among
+  // the first MFMAs, and the offsets of the step after (`kafter`) are computed among the last: this
+  // phase is bound by the matrix pipe and has issue slots to spare, the staging phase has none.
+  auto compute = [&](int kafter) {
 #pragma unroll
     for (int r = 0; r < NR; ++r) lfrag1(0, 0, r);
     __builtin_amdgcn_sched_barrier(0);
@@ -238,38 +246,35 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i < NM; ++i) {
       if (i < NR) lfrag1(1, 1, i);
       mma1(0, i);
+      if (i < 8) gissue(i);
       __builtin_amdgcn_sched_barrier(0);
     }
+    gaddr(kafter);
 #pragma unroll
     for (int i = 0; i < NM; ++i) mma1(1, i);
   };
 
-  // Every wave runs the same loop (compute; barrier; stage, loads, table; barrier); group 1 runs it
+  // Every wave runs the same loop (compute + next loads; barrier; stage, table; barrier); group 1 runs it
   // one barrier late, so that between two barriers one group computes while the other stages.
   const int nsteps = (m_end - m_begin + BKM - 1) / BKM;
   const int nper = (nsteps + 1) >> 1;  // steps per group (rows past m_end load zeros)
   rt_make(0);
   rt_make(1);
+  rt_make(2);
   __syncthreads();
   gload(0);
-  if (grp == 0) {
-    stage();
-    gload(1);
-    rt_make(2);
-  }
+  if (grp == 0) stage();
   __syncthreads();
   if (grp == 1) {
     stage();
-    gload(1);
-    rt_make(2);
     __syncthreads();
   }
+  gaddr(1);
   for (int k = 0; k < nper; ++k) {
-    compute();
+    compute(k + 2);   // issues the loads of step k + 1; reads table slot (k + 2) & 3, written before the last barrier
     __syncthreads();
-    stage();
-    gload(k + 2);
-    rt_make(k + 3);
+    stage();          // step k + 1
+    rt_make(k + 3);   // slot (k + 3) & 3: last read in compute(k - 3)
     __syncthreads();
   }
   if (grp == 0) __syncthreads();  // group 1 started one barrier late

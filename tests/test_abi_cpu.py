@@ -374,3 +374,20 @@ def test_evaluation_calls_validate_before_enqueue(L):
     assert nf.nf_select_exit([5, 9, 9, 7], [10, 30, 20, 40]) == 2
     assert nf.nf_select_exit([5, 9, 9, 7], [10, 20, 30, 40]) == 1
     assert nf.nf_select_exit([4, 4], [7, 7]) == 0
+
+
+def test_contraction_mode_switch():
+    """nf_contraction: returns the previous mode, -1 only queries, unknown modes are refused and
+    leave the mode as it was."""
+    prev = nf.nf_contraction()
+    assert prev in (nf.NF_CONTRACT_F32, nf.NF_CONTRACT_BF16X6)
+    try:
+        assert nf.nf_contraction(nf.NF_CONTRACT_BF16X6) == prev
+        assert nf.nf_contraction() == nf.NF_CONTRACT_BF16X6
+        assert nf.nf_contraction(nf.NF_CONTRACT_F32) == nf.NF_CONTRACT_BF16X6
+        with pytest.raises(nf.NfError) as e:
+            nf.nf_contraction(7)
+        assert e.value.status == nf.NF_ERR_BAD_DESC
+        assert nf.nf_contraction() == nf.NF_CONTRACT_F32
+    finally:
+        nf.nf_contraction(prev)
