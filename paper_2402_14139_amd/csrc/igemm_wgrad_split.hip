@@ -239,12 +239,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // the first MFMAs, and the offsets of the step after (`kafter`) are computed among the last: this
   // phase is bound by the matrix pipe and has issue slots to spare, the staging phase has none.
   auto compute = [&](int kafter) {
+    // fragment reads in the order of first use: the h pieces (needed by the first four MFMAs) go
+    // first and alone, so that the four waves' first MFMAs wait for 16 LDS reads, not 48; the rest
+    // of this slab and all of the next follow one per MFMA
+    constexpr int ORD[12] = {0, 2, 3, 1, 6, 7, 4, 5, 10, 11, 8, 9};
+    static_assert(NR == 12 && NM == 24, "read schedule");
+    __builtin_amdgcn_s_setprio(3);  // the matrix pipe is what the step is sized for: this wave goes first
 #pragma unroll
-    for (int r = 0; r < NR; ++r) lfrag1(0, 0, r);
+    for (int r = 0; r < 4; ++r) lfrag1(0, 0, ORD[r]);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
-      if (i < NR) lfrag1(1, 1, i);
+      if (i < 8) lfrag1(0, 0, ORD[4 + i]);
+      else if (i < 20) lfrag1(1, 1, ORD[i - 8]);
       mma1(0, i);
       if (i < 8) gissue(i);
       __builtin_amdgcn_sched_barrier(0);
@@ -252,6 +259,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     gaddr(kafter);
 #pragma unroll
     for (int i = 0; i < NM; ++i) mma1(1, i);
+    __builtin_amdgcn_s_setprio(0);
   };
 
   // Every wave runs the same loop (compute + next loads; barrier; stage, table; barrier); group 1 runs it
