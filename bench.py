@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 
 # HBM-side bytes per launch (fabric reads + writes) of the kernels that can dominate the default
@@ -280,8 +281,13 @@ def main():
         dom = recs[0]
         if dom["kernel"].startswith("igemm"):
             ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+            # a split-operand kernel spends six bf16 matrix-core multiply-adds per algorithmic one
+            split = "_split_" in dom["kernel"]
+            peak = round(MFMA_BF16_PEAK_TFLOPS / 6.0, 1) if split else MFMA_F32_PEAK_TFLOPS
             roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": round(ach, 2),
-                        "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_F32_PEAK_TFLOPS, 4),
+                        "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
+                        "peak_note": ("bf16 dense matrix peak 2500 TFLOP/s / 6 piece products per fp32 multiply-add"
+                                      if split else "fp32 dense matrix peak"),
                         "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, dom["kernel"])),
                         "traffic_source": TRAFFIC_SOURCE,
                         "launches": dom["launches"], "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // [operand: d, x][group][piece][LDS row][m]: 96 KiB (one array, addressed as such: LDS reached
   // through a converted pointer keeps the compiler from holding the per-thread arrays in registers)
   __shared__ __attribute__((aligned(16))) unsigned short Ts[2][2][3][128][LDH];
-  __shared__ int4 Rt[2][4][BKM];
+  __shared__ int Rt[2][4][4][BKM];  // [group][slot][field][row]: fields read as single words (broadcast reads)
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -99,6 +99,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // ---- staging task of this thread: 8 reduction rows (mg) x 4 columns (pc) of one operand ----
   const int ts = t & 255;
   const bool is_x = w4 >= 2;  // uniform per wave
+  // (lanes along the columns: 512 contiguous bytes per row and load instruction.  The LDS writes of
+  // this mapping have some bank conflicts; with 4 consecutive lanes on the 4 row groups instead they
+  // have none, but the loads then touch 4 rows per 16 lanes and the kernel is 6 % slower)
   const int u = ts & 127, pc = u % 32, mg = u / 32;
   const int wrow = pc;                                   // + 32 * (column within the chunk)
   const int wcol = (mg ^ ((pc >> 2) & 3)) << 3;          // swizzled LDS column of the 8 rows
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       e.y = m < m_end ? hi0 : -(1 << 20);
       e.z = wi0;
       e.w = PROJ ? ((img * p.Hs + ho * p.ss) * p.Ws + wo * p.ss) * p.Cs * 4 : 0;
-      Rt[grp][k & 3][ts] = e;
+      Rt[grp][k & 3][0][ts] = e.x, Rt[grp][k & 3][1][ts] = e.y, Rt[grp][k & 3][2][ts] = e.z, Rt[grp][k & 3][3][ts] = e.w;
     }
   };
 
@@ -167,7 +170,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int4 e = Rt[grp][k & 3][mg * 8 + i];
+        int4 e;
+        e.x = Rt[grp][k & 3][0][mg * 8 + i], e.y = Rt[grp][k & 3][1][mg * 8 + i], e.z = Rt[grp][k & 3][2][mg * 8 + i];
+        e.w = PROJ ? Rt[grp][k & 3][3][mg * 8 + i] : 0;
         if (PROJ && tile_proj) {
           off[i] = (e.w + qc * 4) | ((is_proj & (e.y > -(1 << 19))) ? 0 : OOB);
         } else {
