@@ -167,29 +167,62 @@ __global__ __launch_bounds__(HT) void head_pool_kernel(HeadShape s, float *__res
 // pooled features pq[F] already staged in LDS), log-sum-exp, per-sample loss, dL/dz, and -- the
 // sample's dz being at hand -- the gradient w.r.t. the pooled features
 // dPq[f] = sum_q dz[q] * Wf[q][f], stored to dPq_out (global row of the sample, or an LDS array).
-// z: Cls floats of LDS, red: 8 floats of LDS.
+// z: Cls floats of LDS, red: 8 floats of LDS.  write = false: dz and the loss are formed but not
+// stored (a workgroup that only needs dPq of a sample another workgroup reports).
 __device__ inline void fc_loss_sample(const HeadShape &s, int n, const float *pq, float *z, float *red,
                                       const int32_t *__restrict__ labels, const float *__restrict__ Wf,
                                       const float *__restrict__ bf, float *__restrict__ dz,
-                                      float *__restrict__ loss_n, float *dPq_out) {
+                                      float *__restrict__ loss_n, float *dPq_out, bool write = true) {
   const int t = threadIdx.x;
-  for (int q = t; q < s.Cls; q += HT) {
-    const float *wr = Wf + (long long)q * s.F;
-    float acc = 0.f;
-    if ((s.F & 3) == 0) {
+  const int lane = t & 63, wave = t >> 6;
+  // logits: P threads per class, each over a contiguous 1/P of the features (P a power of two with
+  // P * Cls <= 256 and whole 16-byte groups per part), so that one batch of independent loads per
+  // thread covers the row; the P partial sums are added in order through LDS
+  __shared__ float zp[HT];
+  int P = 1;
+  if ((s.F & 3) == 0)
+    while (P < 8 && 2 * P * s.Cls <= HT && ((s.F >> 2) % (2 * P)) == 0) P *= 2;
+  if (s.Cls <= HT) {
+    const int part = t / s.Cls, q = t - part * s.Cls;
+    if (part < P) {
+      const int fn = s.F / P, f0 = part * fn;
+      const float *wr = Wf + (long long)q * s.F + f0;
+      float acc = 0.f;
+      if ((s.F & 3) == 0) {
 #pragma unroll 8
-      for (int f = 0; f < s.F; f += 4) {
-        const float4 w = *reinterpret_cast<const float4 *>(wr + f);
-        acc += w.x * pq[f] + w.y * pq[f + 1] + w.z * pq[f + 2] + w.w * pq[f + 3];
+        for (int f = 0; f < fn; f += 4) {
+          const float4 w = *reinterpret_cast<const float4 *>(wr + f);
+          acc += w.x * pq[f0 + f] + w.y * pq[f0 + f + 1] + w.z * pq[f0 + f + 2] + w.w * pq[f0 + f + 3];
+        }
+      } else {
+        for (int f = 0; f < fn; ++f) acc += wr[f] * pq[f0 + f];
       }
-    } else {
-      for (int f = 0; f < s.F; ++f) acc += wr[f] * pq[f];
+      zp[t] = acc;
     }
-    z[q] = acc + (bf ? bf[q] : 0.f);
+    __syncthreads();
+    if (t < s.Cls) {
+      float acc = zp[t];
+      for (int k = 1; k < P; ++k) acc += zp[k * s.Cls + t];
+      z[t] = acc + (bf ? bf[t] : 0.f);
+    }
+  } else {
+    for (int q = t; q < s.Cls; q += HT) {
+      const float *wr = Wf + (long long)q * s.F;
+      float acc = 0.f;
+      if ((s.F & 3) == 0) {
+#pragma unroll 8
+        for (int f = 0; f < s.F; f += 4) {
+          const float4 w = *reinterpret_cast<const float4 *>(wr + f);
+          acc += w.x * pq[f] + w.y * pq[f + 1] + w.z * pq[f + 2] + w.w * pq[f + 3];
+        }
+      } else {
+        for (int f = 0; f < s.F; ++f) acc += wr[f] * pq[f];
+      }
+      z[q] = acc + (bf ? bf[q] : 0.f);
+    }
   }
   __syncthreads();
 
-  const int lane = t & 63, wave = t >> 6;
   if (s.mse) {
     // squared error against the one-hot label, mean over the classes (the batch mean follows)
     const int y = labels[n];
@@ -198,12 +231,12 @@ __device__ inline void fc_loss_sample(const HeadShape &s, int n, const float *pq
     for (int q = t; q < s.Cls; q += HT) {
       const float e = z[q] - (q == y ? 1.f : 0.f);
       se += e * e;
-      dz[(long long)n * s.Cls + q] = e * sc;
+      if (write) dz[(long long)n * s.Cls + q] = e * sc;
     }
     se = wave_sum(se);
     if (lane == 0) red[wave] = se;
     __syncthreads();
-    if (t == 0) loss_n[n] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)s.Cls;
+    if (t == 0 && write) loss_n[n] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)s.Cls;
     for (int q = t; q < s.Cls; q += HT) z[q] = (z[q] - (q == y ? 1.f : 0.f)) * sc;
     __syncthreads();
     for (int f = t; f < s.F; f += HT) {
@@ -233,10 +266,10 @@ __device__ inline void fc_loss_sample(const HeadShape &s, int n, const float *pq
   __syncthreads();  // every read of the logits is done: z[] becomes dz[]
   for (int q = t; q < s.Cls; q += HT) {
     const float d = (expf(z[q] - lse) - (q == y ? 1.f : 0.f)) * invB;
-    dz[(long long)n * s.Cls + q] = d;
+    if (write) dz[(long long)n * s.Cls + q] = d;
     z[q] = d;
   }
-  if (t == 0) loss_n[n] = lse - zy;
+  if (t == 0 && write) loss_n[n] = lse - zy;
   __syncthreads();
   for (int f = t; f < s.F; f += HT) {
     float acc = 0.f;
@@ -537,6 +570,50 @@ __global__ __launch_bounds__(HT) void head_sample_kernel(HeadShape s, float *__r
   }
 }
 
+// Everything of the head after F_n for a LARGE activation map in one launch: gamma_n, the loss and
+// dL/dz, dPq, and the backward through F_n and the aux ReLU (dU).  A sample's map is cut into NS
+// slices, one workgroup each, so that the launch has enough workgroups to stream dU; every one of
+// them recomputes the sample's tiny linear layer (F * Cls products, Wf from L2) instead of reading
+// dPq from an earlier launch, and slice 0 stores dz and the per-sample loss.  Workgroups from
+// B * NS on re-lay the aux filter for the data gradient.
+// Dynamic LDS: 2*F + Cls + 8 floats.
+template <int V>
+__global__ __launch_bounds__(HT) void head_wide_kernel(HeadShape s, int NS, const float *__restrict__ U,
+                                                       const float *__restrict__ Pq,
+                                                       const int32_t *__restrict__ labels,
+                                                       const float *__restrict__ Wf, const float *__restrict__ bf,
+                                                       float *__restrict__ dz, float *__restrict__ loss_n,
+                                                       const int32_t *__restrict__ parg, float *__restrict__ dU,
+                                                       const float *__restrict__ Wa, float *__restrict__ WaT, int R,
+                                                       int S, int K) {
+  extern __shared__ float sm[];
+  const int t = threadIdx.x;
+  if ((int)blockIdx.x >= s.B * NS) {
+    const long long i = (long long)(blockIdx.x - s.B * NS) * HT + t;
+    if (i < (long long)s.A * R * S * K) wat_element(i, s.A, R, S, K, Wa, WaT);
+    return;
+  }
+  float *pq = sm;            // [F]
+  float *dpq = pq + s.F;     // [F]
+  float *z = dpq + s.F;      // [Cls]
+  float *red8 = z + s.Cls;   // [8]
+  const int n = blockIdx.x / NS, sl = blockIdx.x - n * NS;
+  for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
+  __syncthreads();
+  fc_loss_sample(s, n, pq, z, red8, labels, Wf, bf, dz, loss_n, dpq, sl == 0);
+  __syncthreads();
+  const int AV = s.A / V, per_n = s.Hu * s.Wu * AV;
+  const int per_sl = (per_n + NS - 1) / NS;
+  const int i1 = min(per_n, (sl + 1) * per_sl);
+  const long long base = (long long)n * per_n;
+  for (int i = sl * per_sl + t; i < i1; i += HT) {
+    const int av = i % AV, r = i / AV;
+    const int w = r % s.Wu, hh = r / s.Wu;
+    du_element<V>(s, hh, w, av, U + (base + i) * V, dpq, s.pmax ? parg + (long long)n * s.F : nullptr,
+                  dU + (base + i) * V);
+  }
+}
+
 // Backward of the head after the softmax in one launch (gradient line of Algorithm 2); the
 // workgroup index selects the job:
 //   [0, nb_w)   gamma_n: one class q and one chunk of `fch` features; the 256 threads are fch
@@ -674,6 +751,33 @@ hipError_t launch_head_sample(const HeadShape &h, float *U, const float *part, i
     else NF_HS(1, false);
   }
 #undef NF_HS
+  return hipGetLastError();
+}
+
+bool head_wide_applicable(const HeadShape &h) {
+  // the linear layer small enough to be recomputed by every slice of a sample (its weights read
+  // from L2 by every workgroup); wider ones share the weights between samples (head_fc_wide_kernel)
+  return !head_sample_applicable(h) && (long long)h.F * h.Cls <= 16384 && h.F <= 1024 && h.Cls <= 1024;
+}
+
+hipError_t launch_head_wide(const HeadShape &h, const float *U, const float *Pq, const int32_t *labels,
+                            const float *Wf, const float *bf, float *dz, float *loss_n, const int32_t *parg,
+                            float *dU, const float *Wa, float *WaT, int R, int S, int K, hipStream_t st) {
+  const int V = h.A % 4 == 0 ? 4 : 1;
+  // slices per sample: about 768 workgroups in all, at least 1024 values of dU each
+  const long long per_sample = (long long)h.Hu * h.Wu * h.A;
+  int NS = (768 + h.B - 1) / h.B;
+  if (NS > per_sample / 1024) NS = (int)(per_sample / 1024);
+  if (NS < 1) NS = 1;
+  const unsigned nb_t = Wa ? (unsigned)(((long long)h.A * R * S * K + HT - 1) / HT) : 0;
+  const dim3 grid((unsigned)(h.B * NS) + nb_t);
+  const size_t lds = (size_t)(2 * h.F + h.Cls + 8) * sizeof(float);
+  if (V == 4)
+    hipLaunchKernelGGL(head_wide_kernel<4>, grid, dim3(HT), lds, st, h, NS, U, Pq, labels, Wf, bf, dz, loss_n, parg, dU,
+                       Wa, WaT, R, S, K);
+  else
+    hipLaunchKernelGGL(head_wide_kernel<1>, grid, dim3(HT), lds, st, h, NS, U, Pq, labels, Wf, bf, dz, loss_n, parg, dU,
+                       Wa, WaT, R, S, K);
   return hipGetLastError();
 }
 

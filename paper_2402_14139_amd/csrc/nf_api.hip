@@ -118,8 +118,9 @@ struct WsLayout {
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
   // reduction splits of the forward-type contractions (1 = none); their partial sums alias `part`
   int ksplits_aux, ksplits_layer, ksplits_dgrad;
-  // the head's per-sample chain (pooling ... dU) runs as one launch right after its convolution;
-  // the batch-reducing rest (gamma_n's gradient, batch-mean loss) rides on the reduction launch
+  // 1: the head's per-sample chain (pooling ... dU) runs as one launch right after its convolution;
+  // 2: as two (pooling; everything else).  In both the batch-reducing rest (gamma_n's gradient,
+  // batch-mean loss) rides on the reduction launch.  0: pooling, linear layer + loss, backward.
   int head_fused;
 };
 
@@ -169,7 +170,7 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     if (w.ksplits_aux > 1 && (size_t)w.ksplits_aux * u > pmax) pmax = (size_t)w.ksplits_aux * u;
     w.ksplits_dgrad = igemm_fwd_pick_ksplits(B * a->H_in * a->W_in, a->C_in, a->R * a->S * a->A, a->A, a->R * a->S);
     if (w.ksplits_dgrad > 1 && (size_t)w.ksplits_dgrad * emitted > pmax) pmax = (size_t)w.ksplits_dgrad * emitted;
-    w.head_fused = head_sample_applicable(head_shape(a, ad, B)) ? 1 : 0;
+    w.head_fused = head_sample_applicable(head_shape(a, ad, B)) ? 1 : head_wide_applicable(head_shape(a, ad, B)) ? 2 : 0;
     w.part_b = take((size_t)w.splits_layer * d->C_out * f);
     w.part_aux = take(pa * f);
     w.part_b_aux = take((size_t)w.splits_aux * a->A * f);
@@ -346,7 +347,7 @@ int32_t run_aux_features(const nf_aux_desc *a, const AuxDims &ad, int B, const f
 int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const int32_t *labels,
                     const nf_aux_params *ap, float *loss_out, void *ws, const WsLayout &w, hipStream_t st) {
   const HeadShape hs = head_shape(a, ad, B);
-  if (w.head_fused) {
+  if (w.head_fused == 1) {
     // small activation map: the convolution, then ONE launch for the head's whole per-sample chain
     // (F_n, gamma_n, loss, dL/dz, dPq, dU) and the re-laid filter the data gradient will read
     FwdProblem f;
@@ -376,6 +377,16 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
   int32_t rc = run_aux_features(a, ad, B, y, ap, ws, w, st);
   if (rc) return rc;
   const double fc = (double)a->n_classes * ad.F;
+  if (w.head_fused == 2) {
+    // large activation map, small linear layer: ONE more launch for gamma_n, loss, dL/dz, dPq and dU
+    const double u = (double)B * ad.Hu * ad.Wu * a->A, wa = (double)a->A * a->R * a->S * a->C_in;
+    NF_RUN(st, "head_wide", 4.0 * B * fc, 4.0 * (2.0 * u + (double)B * (ad.F + a->n_classes + 1.0)) + 8.0 * wa,
+           launch_head_wide(hs, wsf(ws, w.U), wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n),
+                            reinterpret_cast<const int32_t *>(wsf(ws, w.parg)), wsf(ws, w.dU), ap->Wa, wsf(ws, w.WaT),
+                            a->R, a->S, a->C_in, st));
+    if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
+    return NF_OK;
+  }
   NF_RUN(st, "head_fc", 4.0 * B * fc, 4.0 * (2.0 * B * fc + (double)B * (2.0 * ad.F + a->n_classes)),
          launch_head_fc(hs, wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n), wsf(ws, w.dPq), st));
   if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));

@@ -165,6 +165,14 @@ hipError_t launch_head_sample(const HeadShape &h, float *U, const float *part, i
                               const int32_t *labels, const float *Wf, const float *bf, float *Pq, int32_t *parg,
                               float *dz, float *loss_n, float *dU, const float *Wa, float *WaT, int R, int S, int K,
                               hipStream_t st);
+// Everything after F_n for a large activation map in one launch (head_wide_applicable: a linear
+// layer of at most 16384 weights): gamma_n, loss, dL/dz, dPq recomputed per slice of a sample, dU,
+// and the re-laid aux filter when Wa is given.  Reads Pq (and the max-pooling selection) left by
+// launch_head_pool; leaves dz and loss_n for the batch-reducing jobs (GammaJob).
+bool head_wide_applicable(const HeadShape &h);
+hipError_t launch_head_wide(const HeadShape &h, const float *U, const float *Pq, const int32_t *labels,
+                            const float *Wf, const float *bf, float *dz, float *loss_n, const int32_t *parg,
+                            float *dU, const float *Wa, float *WaT, int R, int S, int K, hipStream_t st);
 // one launch: dWf, dbf; dU (pool + aux ReLU backward); WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa
 // is given; the batch-mean loss when loss_out is given
 hipError_t launch_head_bwd(const HeadShape &h, const float *Pq, const float *dz, float *dWf, float *dbf,
