@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 # WRITE_SIZE x 1.0.  Averages over the launches of one step; summary under profiles/.
 TRAFFIC_BYTES_PER_LAUNCH = {
     ("cfg3_resnet18", "igemm_wgrad_fast_128x128"): 66.5e6 + 37.9e6,
-    ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 67.4e6 + 16.8e6,
+    ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 68.1e6 + 16.8e6,
 }
 TRAFFIC_SOURCE = ("offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this script, scaled by a 1 GiB copy "
                   "(FETCH x 2.0, WRITE x 1.0); summary in profiles/local_step_cfg3_hbm_traffic.md; not re-measured "
@@ -45,17 +45,17 @@ TRAFFIC_SOURCE = ("offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over 
 # live below) add about 3 us to every launch, which halves the apparent rate of a 6 us copy.
 HBM_OFFLINE = {
     "cfg3_resnet18": [
-        ("cache_copy_kernel", 1048576, 33.59e6, 6.37), ("cache_copy_kernel", 2097152, 67.15e6, 15.13),
-        ("wgrad_reduce_kernel", 235776, 17.32e6, 7.15), ("wgrad_reduce_kernel", 672512, 46.10e6, 12.17),
-        ("wgrad_reduce_kernel", 2463232, 55.98e6, 17.78), ("wgrad_reduce_kernel", 697856, 141.74e6, 25.75),
-        ("head_pool_kernel<4, false>", 65536, 8.54e6, 6.32), ("head_fc_kernel", 16384, 0.60e6, 9.65),
-        ("head_bwd_kernel<4>", 645376, 18.18e6, 7.32), ("head_sample_kernel<4, false>", 83968, 4.32e6, 12.01),
+        ("cache_copy_kernel", 1048576, 33.59e6, 6.29), ("cache_copy_kernel", 2097152, 67.15e6, 14.71),
+        ("wgrad_reduce_kernel", 325376, 17.62e6, 7.18), ("wgrad_reduce_kernel", 1283584, 50.11e6, 15.19),
+        ("wgrad_reduce_kernel", 402944, 76.87e6, 17.60), ("wgrad_reduce_kernel", 697856, 141.74e6, 25.95),
+        ("head_pool_kernel<4, false>", 65536, 8.53e6, 6.59), ("head_wide_kernel<4>", 215040, 18.43e6, 16.06),
+        ("head_wide_kernel<4>", 149504, 5.44e6, 9.44), ("head_sample_kernel<4, false>", 83968, 4.34e6, 12.68),
     ],
 }
 HBM_OFFLINE_SOURCE = "profiles/local_step_cfg3_hbm_traffic.md (offline rocprofv3 passes; not re-measured by this run)"
 # kernels judged against the HBM roofline (everything that is not a contraction)
 HBM_KERNELS = ("cache_read", "cache_write", "cache_copy", "wgrad_reduce_sgd", "wgrad_reduce", "head_pool", "head_fc",
-               "head_sample", "head_bwd", "maxpool_fwd", "maxpool_bwd", "fwd_finish", "sgd", "loss_mean")
+               "head_sample", "head_wide", "head_bwd", "maxpool_fwd", "maxpool_bwd", "fwd_finish", "sgd", "loss_mean")
 
 
 def layer_flops(ls, B, n_classes):
