@@ -8,10 +8,10 @@
 // together below 2^-23 |x*w|) are left out and the six others are accumulated in fp32 by
 // v_mfma_f32_32x32x16_bf16.  Per multiply-add that is the error of an fp32 multiply followed by an
 // fp32 add; measured against an fp64 sum over 576 ... 4608 terms the result is as close as the
-// one of v_mfma_f32_32x32x2_f32.  Six bf16 MFMAs of 16 reduction steps take the time of 1.2 fp32
-// MFMAs of 2, which cover the same 16 steps with eight: the matrix pipe has 2.5x the work done
-// per cycle, and the kernel is sized so that splitting (vector ALU) and the larger LDS traffic
-// (three pieces per operand) hide under it.
+// one of v_mfma_f32_32x32x2_f32.  Six bf16 MFMAs (8 passes each) cover 16 reduction steps of a
+// 32x32 tile in the time of three fp32 MFMAs (16 passes each), which need eight for the same 16
+// steps: 2.67x the work per matrix-pipe cycle.  What it costs is vector-ALU work for cutting the
+// operands (5.5 instructions per element staged) and 1.5x the LDS bytes (three pieces of 2 bytes).
 //
 // Non-finite inputs: inf - inf appears in the remainders, so an operand element that is +-inf
 // yields NaN where the fp32 kernel would yield +-inf.
@@ -82,8 +82,8 @@ __device__ inline floatx16 mfma_bf16(uint4 a, uint4 b, floatx16 c) {
 // reduction steps alternately (group 0 the even ones), each with its own accumulators (added once
 // at the end, group 0 + group 1) and its own LDS buffer.  Every wave runs the same loop -- the 48
 // MFMAs of a step, with the loads of its next step issued among them; barrier; split the operands
-// of that next step into the buffer; barrier -- but group 1 runs it one barrier late, so that between two barriers
-// one group is in its MFMAs while the other splits.  A wave issues in order and an MFMA that finds
+// of that next step into the buffer; barrier -- but group 1 runs it one barrier late, so that
+// between two barriers one group is in its MFMAs while the other splits.  A wave issues in order and an MFMA that finds
 // the matrix pipe busy holds everything behind it: the vector-ALU work of the split has to come
 // from another wave of the SIMD to overlap with the MFMAs.
 template <bool PROJ, bool TI>
