@@ -98,3 +98,25 @@ def test_split_mode_is_deterministic(split_mode):
             assert np.array_equal(pa[k], pb[k]), k
             if va is not None:
                 assert np.array_equal(va[k], vb[k]), k
+
+
+def test_narrow_layers_are_untouched_by_the_mode():
+    """A 64-filter layer has no wide contraction: both modes run the same kernels, bit for bit."""
+    cfg = workloads.config("cfg3")
+    spec = cfg.layers[1]
+    res = {}
+    for mode in (B.NF_CONTRACT_F32, B.NF_CONTRACT_BF16X6):
+        prev = B.nf_contraction(mode)
+        try:
+            out, final = G.run_step_both(spec, cfg.n_classes, 16, seed=99, lr=cfg.lr, mu=cfg.momentum, steps=1,
+                                         bias_std=0.05)
+        finally:
+            B.nf_contraction(prev)
+        res[mode] = (out[0][0], final[0][0])
+    (la, ga, ya), pa = res[B.NF_CONTRACT_F32]
+    (lb, gb, yb), pb = res[B.NF_CONTRACT_BF16X6]
+    assert la == lb and np.array_equal(ya, yb)
+    for k in G.PARAM_NAMES:
+        if ga[k] is not None:
+            assert np.array_equal(ga[k], gb[k]), k
+            assert np.array_equal(pa[k], pb[k]), k
