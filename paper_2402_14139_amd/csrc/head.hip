@@ -575,11 +575,12 @@ __global__ __launch_bounds__(HT) void head_sample_kernel(HeadShape s, float *__r
 // slices, one workgroup each, so that the launch has enough workgroups to stream dU; every one of
 // them recomputes the sample's tiny linear layer (F * Cls products, Wf from L2) instead of reading
 // dPq from an earlier launch, and slice 0 stores dz and the per-sample loss.  Workgroups from
-// B * NS on re-lay the aux filter for the data gradient.
+// B * NS on re-lay the aux filter for the data gradient.  With `ppart` given, F_n itself is formed
+// here too (and Pq stored by slice 0) from the column sums the aux convolution's epilogue left.
 // Dynamic LDS: 2*F + Cls + 8 floats.
 template <int V>
 __global__ __launch_bounds__(HT) void head_wide_kernel(HeadShape s, int NS, const float *__restrict__ U,
-                                                       const float *__restrict__ Pq,
+                                                       float *__restrict__ Pq, const float *__restrict__ ppart,
                                                        const int32_t *__restrict__ labels,
                                                        const float *__restrict__ Wf, const float *__restrict__ bf,
                                                        float *__restrict__ dz, float *__restrict__ loss_n,
@@ -598,7 +599,39 @@ __global__ __launch_bounds__(HT) void head_wide_kernel(HeadShape s, int NS, cons
   float *z = dpq + s.F;      // [Cls]
   float *red8 = z + s.Cls;   // [8]
   const int n = blockIdx.x / NS, sl = blockIdx.x - n * NS;
-  for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
+  if (ppart) {
+    // F_n (2x2 average pooling of an even-sized map) from the column sums the aux convolution left
+    // per 16 consecutive pixels: image rows of 16 pixels carry both halves in two slots, wider rows
+    // are whole 16-pixel groups per half.  Rows ascending, groups ascending: a fixed order.
+    const bool split = s.Wu == 16;
+    const int gpr = s.Wu >> 4;                // 16-pixel groups per image row
+    const int gph = split ? 1 : (gpr >> 1);   // ... per half row
+    const float inv = 1.f / (float)((s.Hu >> 1) * (s.Wu >> 1));
+    for (int f = t; f < s.F; f += HT) {
+      const int cell = f / s.A, a = f - cell * s.A;
+      const int ci = cell >> 1, cj = cell & 1;
+      // partial i of the cell: image row ci*Hu/2 + i / gph, group i % gph of the half row; loaded
+      // eight at a time (independent loads), added in order
+      const int np = (s.Hu >> 1) * gph;
+      const float *src = ppart + (split ? cj : 0) * s.A + a;
+      float acc = 0.f;
+      for (int i0 = 0; i0 < np; i0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = i0 + u, hr = i / gph;
+          const long long r16 = ((long long)n * s.Hu + ci * (s.Hu >> 1) + hr) * gpr + (split ? 0 : cj * gph + (i - hr * gph));
+          v[u] = i < np ? src[r16 * 2 * s.A] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+      }
+      pq[f] = acc * inv;
+      if (sl == 0) Pq[(long long)n * s.F + f] = acc * inv;
+    }
+  } else {
+    for (int f = t; f < s.F; f += HT) pq[f] = Pq[(long long)n * s.F + f];
+  }
   __syncthreads();
   fc_loss_sample(s, n, pq, z, red8, labels, Wf, bf, dz, loss_n, dpq, sl == 0);
   __syncthreads();
@@ -760,7 +793,13 @@ bool head_wide_applicable(const HeadShape &h) {
   return !head_sample_applicable(h) && (long long)h.F * h.Cls <= 16384 && h.F <= 1024 && h.Cls <= 1024;
 }
 
-hipError_t launch_head_wide(const HeadShape &h, const float *U, const float *Pq, const int32_t *labels,
+bool head_pool_partials_applicable(const HeadShape &h) {
+  // 2x2 average pooling of an even-sized map whose rows are whole groups of 16 pixels per half (or
+  // exactly 16 pixels: the two halves are the two 8-pixel sums of a group)
+  return !h.pmax && h.oh == 2 && h.ow == 2 && h.Hu % 2 == 0 && (h.Wu == 16 || h.Wu % 32 == 0);
+}
+
+hipError_t launch_head_wide(const HeadShape &h, const float *U, float *Pq, const float *ppart, const int32_t *labels,
                             const float *Wf, const float *bf, float *dz, float *loss_n, const int32_t *parg,
                             float *dU, const float *Wa, float *WaT, int R, int S, int K, hipStream_t st) {
   const int V = h.A % 4 == 0 ? 4 : 1;
@@ -773,10 +812,10 @@ hipError_t launch_head_wide(const HeadShape &h, const float *U, const float *Pq,
   const dim3 grid((unsigned)(h.B * NS) + nb_t);
   const size_t lds = (size_t)(2 * h.F + h.Cls + 8) * sizeof(float);
   if (V == 4)
-    hipLaunchKernelGGL(head_wide_kernel<4>, grid, dim3(HT), lds, st, h, NS, U, Pq, labels, Wf, bf, dz, loss_n, parg, dU,
+    hipLaunchKernelGGL(head_wide_kernel<4>, grid, dim3(HT), lds, st, h, NS, U, Pq, ppart, labels, Wf, bf, dz, loss_n, parg, dU,
                        Wa, WaT, R, S, K);
   else
-    hipLaunchKernelGGL(head_wide_kernel<1>, grid, dim3(HT), lds, st, h, NS, U, Pq, labels, Wf, bf, dz, loss_n, parg, dU,
+    hipLaunchKernelGGL(head_wide_kernel<1>, grid, dim3(HT), lds, st, h, NS, U, Pq, ppart, labels, Wf, bf, dz, loss_n, parg, dU,
                        Wa, WaT, R, S, K);
   return hipGetLastError();
 }

@@ -341,6 +341,30 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
       }
     }
   }
+
+  // ---- pooled partial sums for the head (16x16x4 tiles, whole tiles only): the lane's four rows,
+  // then the lane groups 0+1 and 2+3 (rows 0-7, 8-15 of the wave's 16), then both (fixed order) ----
+  if constexpr (MF == 16 && MT == 1) {
+    if (p.pool_part) {
+      const int r16 = (m0 + wm * TM) >> 4;
+#pragma unroll
+      for (int b = 0; b < NT; ++b) {
+        const int n = n0 + wn * TN + b * MF + j;
+        const float bias = (n < p.N && p.bias) ? p.bias[n] : 0.f;
+        float ps = 0.f;
+#pragma unroll
+        for (int e = 0; e < MM::NACC; ++e) {
+          float v = acc[0][b][e] + bias;
+          if (p.relu) v = v > 0.f ? v : 0.f;
+          ps += v;
+        }
+        ps += __shfl_xor(ps, 16, 64);
+        if (!p.pool_split) ps += __shfl_xor(ps, 32, 64);
+        if (n < p.N && (g == 0 || (p.pool_split && g == 2)))
+          p.pool_part[((long long)r16 * 2 + (g >> 1)) * p.N + n] = ps;
+      }
+    }
+  }
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int MF>
@@ -398,6 +422,13 @@ int igemm_fwd_pick_ksplits(int M, int N, int Kg, int C, int taps) {
   if (s > nkb / 8) s = nkb / 8;
   if (s > 32) s = 32;
   return s > 1 ? s : 1;
+}
+
+bool fwd_pool_partials_applicable(const FwdProblem &p) {
+  // the 64x32 / 64x16 tiles of launch_igemm_fwd_fast (16x16x4 MFMA, a wave = 16 consecutive rows),
+  // whole tiles, plain epilogue (bias + ReLU), reduction not split over workgroups
+  return igemm_fwd_fast_applicable(p) && p.N <= 32 && p.M % 64 == 0 && p.ksplits <= 1 && !p.addsrc && !p.mask &&
+         !p.Cs;
 }
 
 bool igemm_fwd_fast_applicable(const FwdProblem &p) {

@@ -113,8 +113,20 @@ HeadShape head_shape(const nf_aux_desc *a, const AuxDims &ad, int B) {
   return h;
 }
 
+// beta_n of Eq. 2 as a forward-type contraction (pointers left null)
+FwdProblem aux_fwd_problem(const nf_aux_desc *a, const AuxDims &ad, int B) {
+  FwdProblem f;
+  std::memset((void *)&f, 0, sizeof(f));
+  f.H = a->H_in, f.W = a->W_in, f.C = a->C_in, f.N = a->A, f.R = a->R, f.S = a->S, f.stride = 1, f.pad = a->pad,
+  f.Ho = ad.Hu, f.Wo = ad.Wu;
+  f.relu = a->relu ? 1 : 0;
+  f.M = B * ad.Hu * ad.Wu, f.RSC = a->R * a->S * a->C_in, f.Kg = f.RSC;
+  f.div_howo = FastDiv(ad.Hu * ad.Wu), f.div_wo = FastDiv(ad.Wu);
+  return f;
+}
+
 struct WsLayout {
-  size_t T_dZ, arg, U, Pq, parg, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, total;
+  size_t T_dZ, arg, U, Pq, parg, dz, loss_n, dPq, dU, WaT, dY, part, part_b, part_aux, part_b_aux, ppart, total;
   int splits_aux, splits_layer, Qld_aux, Qld_layer;
   // reduction splits of the forward-type contractions (1 = none); their partial sums alias `part`
   int ksplits_aux, ksplits_layer, ksplits_dgrad;
@@ -122,6 +134,9 @@ struct WsLayout {
   // 2: as two (pooling; everything else).  In both the batch-reducing rest (gamma_n's gradient,
   // batch-mean loss) rides on the reduction launch.  0: pooling, linear layer + loss, backward.
   int head_fused;
+  // head_fused == 2 only: F_n is formed from column sums left by the aux convolution's epilogue
+  // (region ppart), no pooling launch
+  int pool_fused;
 };
 
 WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *a, const AuxDims &ad, int B) {
@@ -171,6 +186,12 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     w.ksplits_dgrad = igemm_fwd_pick_ksplits(B * a->H_in * a->W_in, a->C_in, a->R * a->S * a->A, a->A, a->R * a->S);
     if (w.ksplits_dgrad > 1 && (size_t)w.ksplits_dgrad * emitted > pmax) pmax = (size_t)w.ksplits_dgrad * emitted;
     w.head_fused = head_sample_applicable(head_shape(a, ad, B)) ? 1 : head_wide_applicable(head_shape(a, ad, B)) ? 2 : 0;
+    if (w.head_fused == 2 && head_pool_partials_applicable(head_shape(a, ad, B))) {
+      FwdProblem fp = aux_fwd_problem(a, ad, B);
+      fp.ksplits = w.ksplits_aux;
+      w.pool_fused = fwd_pool_partials_applicable(fp) ? 1 : 0;
+    }
+    w.ppart = take(w.pool_fused ? (size_t)B * ad.Hu * ad.Wu / 16 * 2 * a->A * f : 0);
     w.part_b = take((size_t)w.splits_layer * d->C_out * f);
     w.part_aux = take(pa * f);
     w.part_b_aux = take((size_t)w.splits_aux * a->A * f);
@@ -320,21 +341,20 @@ int32_t run_layer_fwd(const nf_layer_desc *d, const LayerDims &ld, int B, const 
 // beta_n and F_n of Eq. 2: the head's convolution (+ bias, ReLU) and its pooling; leaves U and Pq
 // (and the max-pooling selection) in the workspace
 int32_t run_aux_features(const nf_aux_desc *a, const AuxDims &ad, int B, const float *y, const nf_aux_params *ap,
-                         void *ws, const WsLayout &w, hipStream_t st) {
-  FwdProblem f;
-  std::memset((void *)&f, 0, sizeof(f));
+                         void *ws, const WsLayout &w, hipStream_t st, bool partials_only = false) {
+  FwdProblem f = aux_fwd_problem(a, ad, B);
   f.x = y, f.w = ap->Wa, f.bias = ap->ba;
-  f.H = a->H_in, f.W = a->W_in, f.C = a->C_in, f.N = a->A, f.R = a->R, f.S = a->S, f.stride = 1, f.pad = a->pad,
-  f.Ho = ad.Hu, f.Wo = ad.Wu;
-  f.relu = a->relu ? 1 : 0;
-  f.M = B * ad.Hu * ad.Wu, f.RSC = a->R * a->S * a->C_in, f.Kg = f.RSC;
-  f.div_howo = FastDiv(ad.Hu * ad.Wu), f.div_wo = FastDiv(ad.Wu);
   // skinny head, long reduction: split it; the pooling kernel adds the parts, bias and ReLU
   const int ks = (w.ksplits_aux > 1 && igemm_fwd_fast_applicable(f)) ? w.ksplits_aux : 0;
   f.ksplits = ks;
   f.out = ks ? wsf(ws, w.part) : wsf(ws, w.U);
+  // partials_only (the caller's next launch forms F_n itself): the convolution's epilogue leaves
+  // the column sums per 16 pixels, and there is no pooling launch
+  const bool fused = partials_only && w.pool_fused;
+  if (fused) f.pool_part = wsf(ws, w.ppart), f.pool_split = ad.Wu == 16 ? 1 : 0;
   int32_t rc = enqueue_fwd(f, st);
   if (rc) return rc;
+  if (fused) return NF_OK;
   const HeadShape hs = head_shape(a, ad, B);
   const double u = (double)B * ad.Hu * ad.Wu * a->A;
   NF_RUN(st, "head_pool", 0.0, 4.0 * (u * (ks ? ks + 1.0 : 1.0) + (double)B * ad.F),
@@ -374,14 +394,14 @@ int32_t run_aux_fwd(const nf_aux_desc *a, const AuxDims &ad, int B, const float 
     if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));
     return NF_OK;
   }
-  int32_t rc = run_aux_features(a, ad, B, y, ap, ws, w, st);
+  int32_t rc = run_aux_features(a, ad, B, y, ap, ws, w, st, w.head_fused == 2);
   if (rc) return rc;
   const double fc = (double)a->n_classes * ad.F;
   if (w.head_fused == 2) {
     // large activation map, small linear layer: ONE more launch for gamma_n, loss, dL/dz, dPq and dU
     const double u = (double)B * ad.Hu * ad.Wu * a->A, wa = (double)a->A * a->R * a->S * a->C_in;
     NF_RUN(st, "head_wide", 4.0 * B * fc, 4.0 * (2.0 * u + (double)B * (ad.F + a->n_classes + 1.0)) + 8.0 * wa,
-           launch_head_wide(hs, wsf(ws, w.U), wsf(ws, w.Pq), labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n),
+           launch_head_wide(hs, wsf(ws, w.U), wsf(ws, w.Pq), w.pool_fused ? wsf(ws, w.ppart) : nullptr, labels, ap->Wf, ap->bf, wsf(ws, w.dz), wsf(ws, w.loss_n),
                             reinterpret_cast<const int32_t *>(wsf(ws, w.parg)), wsf(ws, w.dU), ap->Wa, wsf(ws, w.WaT),
                             a->R, a->S, a->C_in, st));
     if (loss_out) NF_RUN(st, "loss_mean", 0.0, 4.0 * B, launch_loss_mean(wsf(ws, w.loss_n), B, loss_out, st));

@@ -39,7 +39,15 @@ struct FwdProblem {
   // > 1: the reduction is cut into this many parts and `out` is [ksplits][M][N] raw partial sums
   // (no bias, shortcut, ReLU or mask); only with a value igemm_fwd_pick_ksplits returned
   int ksplits;
+  // Column sums of the finished output over groups of 16 consecutive rows, for the head's average
+  // pooling (skinny 16x16x4 tiles only, see fwd_pool_partials_applicable): pool_part[r16][2][N],
+  // slot 0 = the sum over rows 16*r16 .. +7 (pool_split) or .. +15 (!pool_split), slot 1 = rows +8 .. +15
+  // (pool_split only).  Null: not formed.
+  float *pool_part;
+  int pool_split;
 };
+// whether launch_igemm_fwd would run `p` on a tile that can form pool_part (M a multiple of 64)
+bool fwd_pool_partials_applicable(const FwdProblem &p);
 // how many reduction splits a skinny forward-type contraction should use (1 = none)
 int igemm_fwd_pick_ksplits(int M, int N, int Kg, int C, int taps);
 // out[m][n] = act(sum_z part[z][m][n] + bias[n] + addsrc[m][n]) zeroed where mask[m][n] <= 0:
@@ -169,8 +177,11 @@ hipError_t launch_head_sample(const HeadShape &h, float *U, const float *part, i
 // layer of at most 16384 weights): gamma_n, loss, dL/dz, dPq recomputed per slice of a sample, dU,
 // and the re-laid aux filter when Wa is given.  Reads Pq (and the max-pooling selection) left by
 // launch_head_pool; leaves dz and loss_n for the batch-reducing jobs (GammaJob).
+// `ppart` (or null): column sums per 16 pixels from the aux convolution's epilogue
+// (FwdProblem::pool_part, head_pool_partials_applicable); then F_n is formed here as well and Pq written.
 bool head_wide_applicable(const HeadShape &h);
-hipError_t launch_head_wide(const HeadShape &h, const float *U, const float *Pq, const int32_t *labels,
+bool head_pool_partials_applicable(const HeadShape &h);
+hipError_t launch_head_wide(const HeadShape &h, const float *U, float *Pq, const float *ppart, const int32_t *labels,
                             const float *Wf, const float *bf, float *dz, float *loss_n, const int32_t *parg,
                             float *dU, const float *Wa, float *WaT, int R, int S, int K, hipStream_t st);
 // one launch: dWf, dbf; dU (pool + aux ReLU backward); WaT[k][r][s][a] = Wa[a][R-1-r][S-1-s][k] when Wa
