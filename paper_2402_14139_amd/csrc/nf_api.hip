@@ -187,9 +187,11 @@ WsLayout ws_layout(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_des
     if (w.ksplits_dgrad > 1 && (size_t)w.ksplits_dgrad * emitted > pmax) pmax = (size_t)w.ksplits_dgrad * emitted;
     w.head_fused = head_sample_applicable(head_shape(a, ad, B)) ? 1 : head_wide_applicable(head_shape(a, ad, B)) ? 2 : 0;
     if (w.head_fused == 2 && head_pool_partials_applicable(head_shape(a, ad, B))) {
+      // (a reduction split in two gives way: the pooling launch it would need costs more than it gains)
       FwdProblem fp = aux_fwd_problem(a, ad, B);
-      fp.ksplits = w.ksplits_aux;
+      fp.ksplits = w.ksplits_aux <= 2 ? 1 : w.ksplits_aux;
       w.pool_fused = fwd_pool_partials_applicable(fp) ? 1 : 0;
+      if (w.pool_fused) w.ksplits_aux = 1;
     }
     w.ppart = take(w.pool_fused ? (size_t)B * ad.Hu * ad.Wu / 16 * 2 * a->A * f : 0);
     w.part_b = take((size_t)w.splits_layer * d->C_out * f);
