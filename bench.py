@@ -48,8 +48,8 @@ HBM_OFFLINE = {
         ("cache_copy_kernel", 1048576, 33.59e6, 6.29), ("cache_copy_kernel", 2097152, 67.15e6, 14.71),
         ("wgrad_reduce_kernel", 325376, 17.62e6, 7.18), ("wgrad_reduce_kernel", 1283584, 50.11e6, 15.19),
         ("wgrad_reduce_kernel", 402944, 76.87e6, 17.60), ("wgrad_reduce_kernel", 697856, 141.74e6, 25.95),
-        ("head_pool_kernel<4, false>", 65536, 8.53e6, 6.59), ("head_wide_kernel<4>", 215040, 18.43e6, 16.06),
-        ("head_wide_kernel<4>", 149504, 5.44e6, 9.44), ("head_sample_kernel<4, false>", 83968, 4.34e6, 12.68),
+        ("head_wide_kernel<4>", 215040, 22.45e6, 17.66), ("head_wide_kernel<4>", 149504, 6.45e6, 10.60),
+        ("head_sample_kernel<4, false>", 83968, 4.34e6, 12.61),
     ],
 }
 HBM_OFFLINE_SOURCE = "profiles/local_step_cfg3_hbm_traffic.md (offline rocprofv3 passes; not re-measured by this run)"
