@@ -102,14 +102,17 @@ typedef struct {
 const char *nf_strerror(int32_t status);
 
 /* How the wide contractions (the convolution of Eq. 1 and its weight gradient in Algorithm 2, for
- * layers with more than 128 filters) are carried out.  Operands, results and accumulation are fp32
+ * layers with at least 128 filters) are carried out.  Operands, results and accumulation are fp32
  * in both modes.
  *   NF_CONTRACT_F32     (default) fp32 matrix-core instructions (v_mfma_f32_32x32x2_f32).
  *   NF_CONTRACT_BF16X6  each fp32 operand element is cut into three bfloat16 pieces that sum to it
- *                       exactly; six of the nine piece products (all but the three below 2^-23 of
- *                       the product) are accumulated in fp32 by bf16 matrix-core instructions.
- *                       Same error bound per multiply-add as an fp32 multiply followed by an fp32
- *                       add; an operand element that is +-inf gives NaN instead of +-inf.
+ *                       exactly; six of the nine piece products are accumulated in fp32 by bf16
+ *                       matrix-core instructions.  The three left out are together below 2^-21 of
+ *                       the product in the worst case and about 2^-24 of it in the root mean
+ *                       square, i.e. of the size of an fp32 rounding; over the reductions of this
+ *                       library (36 ... 4608 terms) the measured error against fp64 equals that of
+ *                       the fp32 instructions.  An operand element that is +-inf gives NaN
+ *                       instead of +-inf.
  * Process-wide (read when a call enqueues its kernels); returns the previous mode, or
  * NF_ERR_BAD_DESC for an unknown mode.  mode = -1 only queries. */
 enum { NF_CONTRACT_F32 = 0, NF_CONTRACT_BF16X6 = 1 };

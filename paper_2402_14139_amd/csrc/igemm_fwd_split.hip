@@ -4,11 +4,12 @@
 //
 // An fp32 number is the exact sum of three bfloat16 numbers: x = h + m + l, each piece holding 8
 // of the 24 significant bits (pieces are cut by truncation, so every remainder is exact).  A
-// product x*w is then the sum of nine exact piece products; the three smallest (m*l, l*m, l*l,
-// together below 2^-23 |x*w|) are left out and the six others are accumulated in fp32 by
-// v_mfma_f32_32x32x16_bf16.  Per multiply-add that is the error of an fp32 multiply followed by an
-// fp32 add; measured against an fp64 sum over 576 ... 4608 terms the result is as close as the
-// one of v_mfma_f32_32x32x2_f32.  Six bf16 MFMAs (8 passes each) cover 16 reduction steps of a
+// product x*w is then the sum of nine exact piece products; the three smallest (m*l, l*m, l*l:
+// |m| < 2^-7 |x|, |l| < 2^-15 |x|, so together below 2^-21 |x*w| in the worst case and about
+// 2^-24 |x*w| in the root mean square) are left out and the six others are accumulated in fp32 by
+// v_mfma_f32_32x32x16_bf16.  Per multiply-add that is an error of the size of an fp32 rounding;
+// measured against an fp64 sum over 576 ... 4608 terms the result is as close as the one of
+// v_mfma_f32_32x32x2_f32 (both are dominated by the rounding of the running sum).  Six bf16 MFMAs (8 passes each) cover 16 reduction steps of a
 // 32x32 tile in the time of three fp32 MFMAs (16 passes each), which need eight for the same 16
 // steps: 2.67x the work per matrix-pipe cycle.  What it costs is vector-ALU work for cutting the
 // operands (5.5 instructions per element staged) and 1.5x the LDS bytes (three pieces of 2 bytes).
