@@ -80,9 +80,10 @@ def main():
     ap.add_argument("--lr", type=float, default=None, help="override the configuration's learning rate")
     ap.add_argument("--head-pool", choices=["avg", "max"], default="avg", help="the heads' down-sampling F_n")
     ap.add_argument("--loss", choices=["ce", "mse"], default="ce", help="the local loss of Eq. 3")
-    ap.add_argument("--contraction", choices=["f32", "bf16x6"], default="f32",
+    ap.add_argument("--contraction", choices=["f32", "bf16x6", "bf16x9"], default="f32",
                     help="how the wide contractions run: fp32 matrix-core instructions (the default), or "
-                         "bf16 matrix-core instructions on three-way split fp32 operands (same accuracy)")
+                         "bf16 matrix-core instructions on three-way split fp32 operands (six or all nine piece "
+                         "products; same accuracy)")
     ap.add_argument("--trace-loss", action="store_true", help="print every layer's loss after each step (syncs)")
     ap.add_argument("--traffic-calib", action="store_true",
                     help="only run 5 plain copies of 1 GiB (nf_cache_read, contiguous rows): the known-size kernel "
@@ -104,7 +105,8 @@ def main():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
     nf.lib()
-    nf.nf_contraction(nf.NF_CONTRACT_BF16X6 if args.contraction == "bf16x6" else nf.NF_CONTRACT_F32)
+    modes = {"f32": nf.NF_CONTRACT_F32, "bf16x6": nf.NF_CONTRACT_BF16X6, "bf16x9": nf.NF_CONTRACT_BF16X9}
+    nf.nf_contraction(modes[args.contraction])
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.traffic_calib:
@@ -242,7 +244,7 @@ def main():
 
     # ---- the same steps in the other contraction mode (reported beside the headline, never as it) ----
     other_name = "bf16x6" if args.contraction == "f32" else "f32"
-    prev_mode = nf.nf_contraction(nf.NF_CONTRACT_BF16X6 if other_name == "bf16x6" else nf.NF_CONTRACT_F32)
+    prev_mode = nf.nf_contraction(modes[other_name])
     s0 = args.warmup + args.steps
     for s in range(s0, s0 + args.warmup):
         one_step(s)
@@ -282,11 +284,11 @@ def main():
         if dom["kernel"].startswith("igemm"):
             ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
             # a split-operand kernel spends six bf16 matrix-core multiply-adds per algorithmic one
-            split = "_split_" in dom["kernel"]
-            peak = round(MFMA_BF16_PEAK_TFLOPS / 6.0, 1) if split else MFMA_F32_PEAK_TFLOPS
+            split = 6 if "_split_" in dom["kernel"] else 9 if "_split9_" in dom["kernel"] else 0
+            peak = round(MFMA_BF16_PEAK_TFLOPS / split, 1) if split else MFMA_F32_PEAK_TFLOPS
             roofline = {"kernel": dom["kernel"], "bound": "mfma", "achieved": round(ach, 2),
                         "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
-                        "peak_note": ("bf16 dense matrix peak 2500 TFLOP/s / 6 piece products per fp32 multiply-add"
+                        "peak_note": (f"bf16 dense matrix peak 2500 TFLOP/s / {split} piece products per fp32 multiply-add"
                                       if split else "fp32 dense matrix peak"),
                         "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, dom["kernel"])),
                         "traffic_source": TRAFFIC_SOURCE,

@@ -113,9 +113,12 @@ const char *nf_strerror(int32_t status);
  *                       library (36 ... 4608 terms) the measured error against fp64 equals that of
  *                       the fp32 instructions.  An operand element that is +-inf gives NaN
  *                       instead of +-inf.
+ *   NF_CONTRACT_BF16X9  the same with all nine piece products: every product x*w enters the fp32
+ *                       accumulation exactly, as with the fp32 instructions; 1.5x the matrix-core
+ *                       work of BF16X6.
  * Process-wide (read when a call enqueues its kernels); returns the previous mode, or
  * NF_ERR_BAD_DESC for an unknown mode.  mode = -1 only queries. */
-enum { NF_CONTRACT_F32 = 0, NF_CONTRACT_BF16X6 = 1 };
+enum { NF_CONTRACT_F32 = 0, NF_CONTRACT_BF16X6 = 1, NF_CONTRACT_BF16X9 = 2 };
 int32_t nf_contraction(int32_t mode);
 
 /* Emitted sizes: conv output (Ho,Wo) and post-pool (Hp,Wp).  Any out pointer may be NULL. */

@@ -18,7 +18,7 @@ NF_ERR_NULL, NF_ERR_BAD_DESC, NF_ERR_UNSUPPORTED, NF_ERR_WORKSPACE, NF_ERR_CACHE
     -1, -2, -3, -4, -5, -6)
 NF_ERR_SCRATCH_LIMIT = -7
 NF_STATIC_SCRATCH_BYTES = 128 << 20
-NF_CONTRACT_F32, NF_CONTRACT_BF16X6 = 0, 1
+NF_CONTRACT_F32, NF_CONTRACT_BF16X6, NF_CONTRACT_BF16X9 = 0, 1, 2
 
 EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_fwd", "nf_aux_fwd_loss",
            "nf_local_bwd_wgrad", "nf_sgd_update", "nf_cache_write", "nf_cache_read", "nf_local_step",
@@ -387,7 +387,7 @@ def nf_select_exit(n_correct, n_params) -> int:
 
 
 def nf_contraction(mode: int = -1) -> int:
-    """Sets the process-wide contraction mode (NF_CONTRACT_F32 / NF_CONTRACT_BF16X6) and returns the
+    """Sets the process-wide contraction mode (NF_CONTRACT_F32 / NF_CONTRACT_BF16X6 / NF_CONTRACT_BF16X9) and returns the
     previous one; mode = -1 only queries."""
     rc = int(lib().nf_contraction(int(mode)))
     if rc < 0:

@@ -441,7 +441,8 @@ bool igemm_fwd_fast_applicable(const FwdProblem &p) {
 }
 
 hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char **kernel) {
-  if (contraction_mode() == NF_CONTRACT_BF16X6 && igemm_fwd_split_applicable(p)) return launch_igemm_fwd_split(p, st, kernel);
+  if (contraction_mode() != NF_CONTRACT_F32 && igemm_fwd_split_applicable(p))
+    return launch_igemm_fwd_split(p, contraction_mode() == NF_CONTRACT_BF16X9, st, kernel);
   FastAux q;
   const long long B = p.M / ((long long)p.Ho * p.Wo);
   q.div_c = FastDiv(p.C), q.div_s = FastDiv(p.S);

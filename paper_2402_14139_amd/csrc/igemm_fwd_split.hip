@@ -87,7 +87,8 @@ __device__ inline floatx16 mfma_bf16(uint4 a, uint4 b, floatx16 c) {
 // between two barriers one group is in its MFMAs while the other splits.  A wave issues in order and an MFMA that finds
 // the matrix pipe busy holds everything behind it: the vector-ALU work of the split has to come
 // from another wave of the SIMD to overlap with the MFMAs.
-template <bool PROJ, bool TI>
+// NP: piece products per multiply-add: 6 (m*l, l*m, l*l left out) or all 9.
+template <bool PROJ, bool TI, int NP>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void igemm_fwd_split_kernel(FwdProblem p, SplitAux q) {
   constexpr int BM = 128, BN = 128, BK = 32;
   constexpr int GT = 256;            // threads per group
@@ -266,11 +267,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     else
       bfr[slot][pc][i - MT] = *reinterpret_cast<const uint4 *>(&Bs[buf][pc][wn * TN + (i - MT) * 32 + j][rcol[ks]]);
   };
-  // MFMA i of a slab: the six piece products in the order their fragments are read (h, m, l); the
+  // MFMA i of a slab: the piece products in the order their fragments are read (h, m, l); the
   // tiles innermost, so that MT*NT independent accumulators lie between two MFMAs on the same one
-  constexpr int NM = 6 * MT * NT;  // MFMAs per slab
+  static_assert(NP == 6 || NP == 9, "piece products");
+  constexpr int NM = NP * MT * NT;  // MFMAs per slab
   auto mma1 = [&](int slot, int i) {
-    constexpr int PCA[6] = {0, 0, 1, 1, 0, 2}, PCB[6] = {0, 1, 0, 1, 2, 0};
+    constexpr int PCA[9] = {0, 0, 1, 1, 0, 2, 1, 2, 2}, PCB[9] = {0, 1, 0, 1, 2, 0, 2, 1, 2};
     const int pr = i / (MT * NT), a = (i / NT) % MT, b = i % NT;
     acc[a][b] = mfma_bf16(af[slot][PCA[pr]][a], bfr[slot][PCB[pr]][b], acc[a][b]);
   };
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // first and alone, so that the four waves' first MFMAs wait for 16 LDS reads, not 48; the rest
     // of this slab and all of the next follow one per MFMA
     constexpr int ORD[12] = {0, 2, 3, 1, 6, 7, 4, 5, 10, 11, 8, 9};
-    static_assert(NR == 12 && NM == 24, "read schedule");
+    static_assert(NR == 12 && NM >= 24, "read schedule");
     __builtin_amdgcn_s_setprio(3);  // the matrix pipe is what the step is sized for: this wave goes first
 #pragma unroll
     for (int r = 0; r < 4; ++r) lfrag1(0, 0, ORD[r]);
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-hipError_t launch_cfg(const FwdProblem &p, SplitAux q, hipStream_t st) {
+hipError_t launch_cfg(const FwdProblem &p, SplitAux q, bool nine, hipStream_t st) {
   constexpr int BM = 128, BN = 128, BK = 32;
   const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   q.nkb_conv = (p.RSC + BK - 1) / BK;
@@ -397,7 +399,11 @@ hipError_t launch_cfg(const FwdProblem &p, SplitAux q, hipStream_t st) {
   q.kb_per = (nkb + splits - 1) / splits;
   const dim3 grid((unsigned)tiles, (unsigned)splits), block(512);
   const bool ti = p.C % BK == 0 && p.R * p.S > 1;
-#define NF_LAUNCH(PROJ_, TI_) hipLaunchKernelGGL((igemm_fwd_split_kernel<PROJ_, TI_>), grid, block, 0, st, p, q)
+#define NF_LAUNCH(PROJ_, TI_)                                                                        \
+  do {                                                                                               \
+    if (nine) hipLaunchKernelGGL((igemm_fwd_split_kernel<PROJ_, TI_, 9>), grid, block, 0, st, p, q); \
+    else hipLaunchKernelGGL((igemm_fwd_split_kernel<PROJ_, TI_, 6>), grid, block, 0, st, p, q);      \
+  } while (0)
   if (ti) {
     if (q.nkb_proj) NF_LAUNCH(true, true);
     else NF_LAUNCH(false, true);
@@ -415,7 +421,7 @@ hipError_t launch_cfg(const FwdProblem &p, SplitAux q, hipStream_t st) {
 // the wide tile only: many filters and a reduction of more than five steps
 bool igemm_fwd_split_applicable(const FwdProblem &p) { return p.N >= 128 && p.Kg > 160; }
 
-hipError_t launch_igemm_fwd_split(const FwdProblem &p, hipStream_t st, const char **kernel) {
+hipError_t launch_igemm_fwd_split(const FwdProblem &p, bool nine, hipStream_t st, const char **kernel) {
   SplitAux q;
   const long long B = p.M / ((long long)p.Ho * p.Wo);
   q.div_c = FastDiv(p.C), q.div_s = FastDiv(p.S);
@@ -424,8 +430,8 @@ hipError_t launch_igemm_fwd_split(const FwdProblem &p, hipStream_t st, const cha
   q.xs_bytes = p.Cs ? (uint32_t)(B * p.Hs * p.Ws * p.Cs * 4) : 0;
   q.wp_bytes = p.Cs ? (uint32_t)((long long)p.N * p.Cs * 4) : 0;
   q.nkb_conv = q.nkb_proj = 0;
-  *kernel = "igemm_fwd_split_128x128";
-  return launch_cfg(p, q, st);
+  *kernel = nine ? "igemm_fwd_split9_128x128" : "igemm_fwd_split_128x128";
+  return launch_cfg(p, q, nine, st);
 }
 
 }  // namespace nf

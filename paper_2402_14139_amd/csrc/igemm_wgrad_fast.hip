@@ -329,7 +329,8 @@ bool igemm_wgrad_fast_applicable(const WgradProblem &p) {
 }
 
 hipError_t launch_igemm_wgrad_fast(const WgradProblem &p0, hipStream_t st, const char **kernel) {
-  if (contraction_mode() == NF_CONTRACT_BF16X6 && igemm_wgrad_split_applicable(p0)) return launch_igemm_wgrad_split(p0, st, kernel);
+  if (contraction_mode() != NF_CONTRACT_F32 && igemm_wgrad_split_applicable(p0))
+    return launch_igemm_wgrad_split(p0, contraction_mode() == NF_CONTRACT_BF16X9, st, kernel);
   WgradProblem p = p0;
   const long long B = p.M / ((long long)p.Ho * p.Wo);
   p.d_bytes = (uint32_t)((long long)p.M * p.P * 4);

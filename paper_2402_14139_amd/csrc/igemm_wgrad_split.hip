@@ -65,7 +65,8 @@ __device__ inline floatx16 mfma_bf16(uint4 a, uint4 b, floatx16 c) {
 // PROJ: the q axis ends with the channels of the 1x1 projection shortcut; RSC is a multiple of the
 // tile width, so a tile is all filter taps or all projection channels (its source is picked per
 // workgroup).
-template <bool PROJ>
+// NP: piece products per multiply-add: 6 (m*l, l*m, l*l left out) or all 9.
+template <bool PROJ, int NP>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void igemm_wgrad_split_kernel(WgradProblem p) {
   constexpr int BP = 128, BQ = 128;
   constexpr int MT = 2, NT = 2;  // 32x32 MFMA tiles per wave: 64x64
@@ -230,11 +231,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     else
       bfr[slot][pcs][i - MT] = *reinterpret_cast<const uint4 *>(&Ts[1][buf][pcs][wn * 64 + (i - MT) * 32 + j][rcol[ks]]);
   };
-  // MFMA i of a slab: the six piece products in the order their fragments are read (h, m, l); the
+  // MFMA i of a slab: the piece products in the order their fragments are read (h, m, l); the
   // tiles innermost, so that MT*NT independent accumulators lie between two MFMAs on the same one
-  constexpr int NM = 6 * MT * NT;
+  static_assert(NP == 6 || NP == 9, "piece products");
+  constexpr int NM = NP * MT * NT;
   auto mma1 = [&](int slot, int i) {
-    constexpr int PCA[6] = {0, 0, 1, 1, 0, 2}, PCB[6] = {0, 1, 0, 1, 2, 0};
+    constexpr int PCA[9] = {0, 0, 1, 1, 0, 2, 1, 2, 2}, PCB[9] = {0, 1, 0, 1, 2, 0, 2, 1, 2};
     const int pr = i / (MT * NT), a = (i / NT) % MT, b = i % NT;
     acc[a][b] = mfma_bf16(af[slot][PCA[pr]][a], bfr[slot][PCB[pr]][b], acc[a][b]);
   };
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // first and alone, so that the four waves' first MFMAs wait for 16 LDS reads, not 48; the rest
     // of this slab and all of the next follow one per MFMA
     constexpr int ORD[12] = {0, 2, 3, 1, 6, 7, 4, 5, 10, 11, 8, 9};
-    static_assert(NR == 12 && NM == 24, "read schedule");
+    static_assert(NR == 12 && NM >= 24, "read schedule");
     __builtin_amdgcn_s_setprio(3);  // the matrix pipe is what the step is sized for: this wave goes first
 #pragma unroll
     for (int r = 0; r < 4; ++r) lfrag1(0, 0, ORD[r]);
@@ -363,18 +365,22 @@ bool igemm_wgrad_split_applicable(const WgradProblem &p) {
   return true;
 }
 
-hipError_t launch_igemm_wgrad_split(const WgradProblem &p0, hipStream_t st, const char **kernel) {
+hipError_t launch_igemm_wgrad_split(const WgradProblem &p0, bool nine, hipStream_t st, const char **kernel) {
   WgradProblem p = p0;
   const long long B = p.M / ((long long)p.Ho * p.Wo);
   p.d_bytes = (uint32_t)((long long)p.M * p.P * 4);
   p.x_bytes = (uint32_t)(B * p.H * p.W * p.C * 4);
   p.xs_bytes = p.Cs ? (uint32_t)(B * p.Hs * p.Ws * p.Cs * 4) : 0;
-  *kernel = "igemm_wgrad_split_128x128";
+  *kernel = nine ? "igemm_wgrad_split9_128x128" : "igemm_wgrad_split_128x128";
   const dim3 grid((p.Q + 127) / 128, (p.P + 127) / 128, p.splits);
-  if (p.Cs)
-    hipLaunchKernelGGL((igemm_wgrad_split_kernel<true>), grid, dim3(512), 0, st, p);
+  if (p.Cs && nine)
+    hipLaunchKernelGGL((igemm_wgrad_split_kernel<true, 9>), grid, dim3(512), 0, st, p);
+  else if (p.Cs)
+    hipLaunchKernelGGL((igemm_wgrad_split_kernel<true, 6>), grid, dim3(512), 0, st, p);
+  else if (nine)
+    hipLaunchKernelGGL((igemm_wgrad_split_kernel<false, 9>), grid, dim3(512), 0, st, p);
   else
-    hipLaunchKernelGGL((igemm_wgrad_split_kernel<false>), grid, dim3(512), 0, st, p);
+    hipLaunchKernelGGL((igemm_wgrad_split_kernel<false, 6>), grid, dim3(512), 0, st, p);
   return hipGetLastError();
 }
 

@@ -628,7 +628,7 @@ extern "C" {
 
 int32_t nf_contraction(int32_t mode) {
   if (mode == -1) return nf::g_contraction.load();
-  if (mode != NF_CONTRACT_F32 && mode != NF_CONTRACT_BF16X6) return NF_ERR_BAD_DESC;
+  if (mode != NF_CONTRACT_F32 && mode != NF_CONTRACT_BF16X6 && mode != NF_CONTRACT_BF16X9) return NF_ERR_BAD_DESC;
   return nf::g_contraction.exchange(mode);
 }
 

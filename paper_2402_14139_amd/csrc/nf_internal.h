@@ -60,12 +60,13 @@ hipError_t launch_igemm_fwd(const FwdProblem &p, hipStream_t st, const char **ke
 bool igemm_fwd_fast_applicable(const FwdProblem &p);
 hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char **kernel);
 
-// current contraction mode (nf_contraction): NF_CONTRACT_F32 or NF_CONTRACT_BF16X6
+// current contraction mode (nf_contraction): NF_CONTRACT_F32, NF_CONTRACT_BF16X6 or NF_CONTRACT_BF16X9
 int contraction_mode();
 // fp32 contraction on the bf16 matrix cores through three-way split operands (igemm_fwd_split.hip);
-// launch_igemm_fwd_fast hands over to it in NF_CONTRACT_BF16X6 mode when applicable
+// launch_igemm_fwd_fast hands over to it in the NF_CONTRACT_BF16X* modes when applicable (nine: all
+// nine piece products instead of six)
 bool igemm_fwd_split_applicable(const FwdProblem &p);
-hipError_t launch_igemm_fwd_split(const FwdProblem &p, hipStream_t st, const char **kernel);
+hipError_t launch_igemm_fwd_split(const FwdProblem &p, bool nine, hipStream_t st, const char **kernel);
 
 // first-layer shapes (stem.hip): the whole reduction R*S*C <= 32 in one staging step, channel counts
 // that are not multiples of 4; launch_igemm_fwd / launch_igemm_wgrad pick them when applicable
@@ -91,9 +92,9 @@ hipError_t launch_igemm_wgrad(const WgradProblem &p, hipStream_t st, const char 
 bool igemm_wgrad_fast_applicable(const WgradProblem &p);
 hipError_t launch_igemm_wgrad_fast(const WgradProblem &p, hipStream_t st, const char **kernel);
 // fp32 weight gradient on the bf16 matrix cores through three-way split operands
-// (igemm_wgrad_split.hip); launch_igemm_wgrad_fast hands over to it in NF_CONTRACT_BF16X6 mode
+// (igemm_wgrad_split.hip); launch_igemm_wgrad_fast hands over to it in the NF_CONTRACT_BF16X* modes
 bool igemm_wgrad_split_applicable(const WgradProblem &p);
-hipError_t launch_igemm_wgrad_split(const WgradProblem &p, hipStream_t st, const char **kernel);
+hipError_t launch_igemm_wgrad_split(const WgradProblem &p, bool nine, hipStream_t st, const char **kernel);
 // 3x3 / stride 1 / pad 1 with at most 32 output channels (igemm_wgrad_small.hip): 4x4x1 MFMA with a
 // sliding register window; `splits` are ranges of image rows there (any count is valid)
 bool igemm_wgrad_small_applicable(const WgradProblem &p);

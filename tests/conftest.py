@@ -21,14 +21,15 @@ def oracle():
 
 @pytest.fixture(scope="session", autouse=True)
 def contraction_mode():
-    """NF_CONTRACTION=bf16x6 runs the whole suite with the wide contractions on the bf16 matrix
-    cores (three-way split operands); unset or f32: the default fp32 matrix-core instructions."""
+    """NF_CONTRACTION=bf16x6 (or bf16x9) runs the whole suite with the wide contractions on the bf16
+    matrix cores (three-way split operands, six or nine piece products); unset or f32: the default
+    fp32 matrix-core instructions."""
     want = os.environ.get("NF_CONTRACTION", "")
     if want in ("", "f32"):
         yield
         return
-    assert want == "bf16x6", f"NF_CONTRACTION={want!r}: expected f32 or bf16x6"
+    assert want in ("bf16x6", "bf16x9"), f"NF_CONTRACTION={want!r}: expected f32, bf16x6 or bf16x9"
     from paper_2402_14139_amd import binding as B
-    prev = B.nf_contraction(B.NF_CONTRACT_BF16X6)
+    prev = B.nf_contraction(B.NF_CONTRACT_BF16X6 if want == "bf16x6" else B.NF_CONTRACT_BF16X9)
     yield
     B.nf_contraction(prev)

@@ -380,8 +380,10 @@ def test_contraction_mode_switch():
     """nf_contraction: returns the previous mode, -1 only queries, unknown modes are refused and
     leave the mode as it was."""
     prev = nf.nf_contraction()
-    assert prev in (nf.NF_CONTRACT_F32, nf.NF_CONTRACT_BF16X6)
+    assert prev in (nf.NF_CONTRACT_F32, nf.NF_CONTRACT_BF16X6, nf.NF_CONTRACT_BF16X9)
     try:
+        assert nf.nf_contraction(nf.NF_CONTRACT_BF16X9) == prev
+        assert nf.nf_contraction(prev) == nf.NF_CONTRACT_BF16X9
         assert nf.nf_contraction(nf.NF_CONTRACT_BF16X6) == prev
         assert nf.nf_contraction() == nf.NF_CONTRACT_BF16X6
         assert nf.nf_contraction(nf.NF_CONTRACT_F32) == nf.NF_CONTRACT_BF16X6

@@ -1,10 +1,11 @@
-"""GPU parity of the optional contraction mode NF_CONTRACT_BF16X6: the wide convolutions and weight
-gradients on the bf16 matrix cores, each fp32 operand cut into three bfloat16 pieces.
+"""GPU parity of the optional contraction modes NF_CONTRACT_BF16X6 / NF_CONTRACT_BF16X9: the wide
+convolutions and weight gradients on the bf16 matrix cores, each fp32 operand cut into three bfloat16
+pieces, six or all nine piece products per multiply-add.
 
 Same oracle, same seeded inputs, same tolerances (1e-4 relative; ReLU / arg-max decisions compared
 inside the oracle's own tie band) as the default mode: the mode is a different way to carry out an
 fp32 contraction, not a lower precision.  The whole GPU suite can also be run in this mode with
-NF_CONTRACTION=bf16x6 in the environment.
+NF_CONTRACTION=bf16x6 (or bf16x9) in the environment.
 """
 import numpy as np
 import pytest
@@ -16,20 +17,24 @@ from tests import gpu_common as G
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture()
-def split_mode():
-    prev = B.nf_contraction(B.NF_CONTRACT_BF16X6)
-    yield
+MODES = {"bf16x6": B.NF_CONTRACT_BF16X6, "bf16x9": B.NF_CONTRACT_BF16X9}
+
+
+@pytest.fixture(params=list(MODES))
+def split_mode(request):
+    prev = B.nf_contraction(MODES[request.param])
+    yield request.param
     B.nf_contraction(prev)
 
 
 def _run(cfg_name, li, batch, steps=1):
     cfg = workloads.config(cfg_name)
     spec = cfg.layers[li]
-    print(f"{cfg_name} layer {li} ({spec.name}) B={batch} bf16x6", flush=True)
+    mode = {v: k for k, v in MODES.items()}[B.nf_contraction()]
+    print(f"{cfg_name} layer {li} ({spec.name}) B={batch} {mode}", flush=True)
     out, final = G.run_step_both(spec, cfg.n_classes, batch, seed=cfg.seed * 100 + li, lr=cfg.lr, mu=cfg.momentum,
                                  steps=steps, bias_std=0.05)
-    G.check_step_results(f"{cfg_name}[{li}] bf16x6", out, final)
+    G.check_step_results(f"{cfg_name}[{li}] {mode}", out, final)
     return out, final
 
 
@@ -55,15 +60,15 @@ def test_ragged_batches_two_steps(split_mode, cfg_name, li, batch):
 
 
 def test_mode_changes_the_kernels_and_keeps_the_accuracy():
-    """One 512-filter layer in both modes against the fp64 oracle: the forward output's error in the
-    split mode stays within twice the error of the fp32 matrix-core instructions (measured: equal),
-    and the two modes do differ in the last bits (i.e. the switch reaches the kernels)."""
+    """One 512-filter layer in all modes against the fp64 oracle: the forward output's error in the
+    split modes stays within twice the error of the fp32 matrix-core instructions (measured: equal),
+    and the modes do differ in the last bits (i.e. the switch reaches the kernels)."""
     cfg = workloads.config("cfg3")
     li = 15
     spec = cfg.layers[li]
     batch = 64
     errs, ys = {}, {}
-    for mode in (B.NF_CONTRACT_F32, B.NF_CONTRACT_BF16X6):
+    for mode in (B.NF_CONTRACT_F32, B.NF_CONTRACT_BF16X6, B.NF_CONTRACT_BF16X9):
         prev = B.nf_contraction(mode)
         try:
             out, _ = G.run_step_both(spec, cfg.n_classes, batch, seed=777, lr=cfg.lr, mu=cfg.momentum, steps=1,
@@ -73,9 +78,12 @@ def test_mode_changes_the_kernels_and_keeps_the_accuracy():
         (_, _, gy), (_, _, oy), _ = out[0]
         errs[mode] = float(np.sqrt(np.mean((np.asarray(gy, dtype=np.float64) - np.asarray(oy, dtype=np.float64)) ** 2)))
         ys[mode] = np.asarray(gy)
-    print(f"rms error of y against the oracle: fp32 MFMA {errs[0]:.3e}, bf16x6 {errs[1]:.3e}", flush=True)
+    print(f"rms error of y against the oracle: fp32 MFMA {errs[0]:.3e}, bf16x6 {errs[1]:.3e}, "
+          f"bf16x9 {errs[2]:.3e}", flush=True)
     assert errs[B.NF_CONTRACT_BF16X6] <= 2.0 * errs[B.NF_CONTRACT_F32] + 1e-9
+    assert errs[B.NF_CONTRACT_BF16X9] <= 2.0 * errs[B.NF_CONTRACT_F32] + 1e-9
     assert not np.array_equal(ys[0], ys[1])
+    assert not np.array_equal(ys[0], ys[2])
 
 
 def test_split_mode_is_deterministic(split_mode):
@@ -105,7 +113,7 @@ def test_narrow_layers_are_untouched_by_the_mode():
     cfg = workloads.config("cfg3")
     spec = cfg.layers[1]
     res = {}
-    for mode in (B.NF_CONTRACT_F32, B.NF_CONTRACT_BF16X6):
+    for mode in (B.NF_CONTRACT_F32, B.NF_CONTRACT_BF16X6, B.NF_CONTRACT_BF16X9):
         prev = B.nf_contraction(mode)
         try:
             out, final = G.run_step_both(spec, cfg.n_classes, 16, seed=99, lr=cfg.lr, mu=cfg.momentum, steps=1,
@@ -114,9 +122,10 @@ def test_narrow_layers_are_untouched_by_the_mode():
             B.nf_contraction(prev)
         res[mode] = (out[0][0], final[0][0])
     (la, ga, ya), pa = res[B.NF_CONTRACT_F32]
-    (lb, gb, yb), pb = res[B.NF_CONTRACT_BF16X6]
-    assert la == lb and np.array_equal(ya, yb)
-    for k in G.PARAM_NAMES:
-        if ga[k] is not None:
-            assert np.array_equal(ga[k], gb[k]), k
-            assert np.array_equal(pa[k], pb[k]), k
+    for other in (B.NF_CONTRACT_BF16X6, B.NF_CONTRACT_BF16X9):
+        (lb, gb, yb), pb = res[other]
+        assert la == lb and np.array_equal(ya, yb)
+        for k in G.PARAM_NAMES:
+            if ga[k] is not None:
+                assert np.array_equal(ga[k], gb[k]), k
+                assert np.array_equal(pa[k], pb[k]), k
