@@ -17,6 +17,10 @@
 
 #include "nf_internal.h"
 
+#ifndef NF_FWD_FENCE
+#define NF_FWD_FENCE 1
+#endif
+
 namespace nf {
 namespace {
 
@@ -245,9 +249,22 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
     for (int ks = 0; ks + 1 < NKS; ++ks) {
       lfrag(par, ks + 1, (ks + 1) & 1);
       mma(ks & 1);
+      if constexpr (NF_FWD_FENCE && SCHED && NKS > 2) {
+        if (ks + 2 == NKS) lstore(par ^ 1, par ^ 1);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          if (ks == 1 && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          if (ks + 2 == NKS && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+          if (ks != 0) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // fragment reads stay in the sub-step they were written in
+      }
     }
-    lstore(par ^ 1, par ^ 1);  // step kb+1
-    if constexpr (SCHED) {
+    if constexpr (!(NF_FWD_FENCE && SCHED && NKS > 2)) lstore(par ^ 1, par ^ 1);  // step kb+1
+    if constexpr (SCHED && !(NF_FWD_FENCE && NKS > 2)) {
 #pragma unroll
       for (int ks = 0; ks + 1 < NKS; ++ks) {
         const bool first = ks == 0, last = ks + 2 == NKS;

@@ -143,48 +143,61 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
     Rt[s & 1][t & (BKM - 1)] = e;
   };
 
-  // Branch-free gather of staging step `s` into register set `set` (reads Rt[s & 1]).
-  auto gload = [&](int s, int set) {
-    const int mb = m_begin + s * BKM;
+  // Branch-free gather of staging step `s` into register set `set` (the X rows go by the table entries
+  // tread(s) fetched from Rt[s & 1]), one staged row per call so that the step can place the loads
+  // between its MFMAs.
+  auto gload_d = [&](int s, int set, int i) {
+    const int m = m_begin + s * BKM + rowp + RP * i;
+    const bool ok = (m < m_end) & (dcol_off != OOB);
+    rd[set][i] = bload(rsd, (m * p.P * 4 + dcol_off) | (ok ? 0 : OOB));
+  };
+  int4 te[NQ];  // this thread's table entries of the step being loaded
+  auto tread = [&](int s) {
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      const int m = mb + rowp + RP * i;
-      const bool ok = (m < m_end) & (dcol_off != OOB);
-      rd[set][i] = bload(rsd, (m * p.P * 4 + dcol_off) | (ok ? 0 : OOB));
-    }
-#pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      const int4 e = Rt[s & 1][rowq + RQ * i];
-      const bool ok = is_tap & ((unsigned)(e.y + qr) < (unsigned)p.H) & ((unsigned)(e.z + qs) < (unsigned)p.W);
-      // the offset is formed unconditionally and pushed out of range by its top bit: a select would
-      // let the compiler sink the table read into a branch
-      float4 v;
-      if constexpr (PROJ == 2) {
-        // bit selects with the workgroup-uniform mask: a ?: here would be turned into branches
-        const int okp = (is_proj & (e.y > -(1 << 19))) ? 0 : OOB, okt = ok ? 0 : OOB;
-        const int off = (((e.w + qc * 4) | okp) & proj_mask) | (((e.x + xtap_off) | okt) & ~proj_mask);
-        v = bload(rs_sel, off);
-      } else {
-        v = bload(rsx, (e.x + xtap_off) | (ok ? 0 : OOB));
-        if constexpr (PROJ == 1) {
-          const bool okp = is_proj & (e.y > -(1 << 19));
-          const float4 u = bload(rsxs, (e.w + qc * 4) | (okp ? 0 : OOB));
-          v.x += u.x, v.y += u.y, v.z += u.z, v.w += u.w;  // one of the two is all zeros
-        }
+    for (int i = 0; i < NQ; ++i) te[i] = Rt[s & 1][rowq + RQ * i];
+  };
+  auto gload_x = [&](int set, int i) {
+    const int4 e = te[i];
+    const bool ok = is_tap & ((unsigned)(e.y + qr) < (unsigned)p.H) & ((unsigned)(e.z + qs) < (unsigned)p.W);
+    // the offset is formed unconditionally and pushed out of range by its top bit: a select would
+    // let the compiler sink the table read into a branch
+    float4 v;
+    if constexpr (PROJ == 2) {
+      // bit selects with the workgroup-uniform mask: a ?: here would be turned into branches
+      const int okp = (is_proj & (e.y > -(1 << 19))) ? 0 : OOB, okt = ok ? 0 : OOB;
+      const int off = (((e.w + qc * 4) | okp) & proj_mask) | (((e.x + xtap_off) | okt) & ~proj_mask);
+      v = bload(rs_sel, off);
+    } else {
+      v = bload(rsx, (e.x + xtap_off) | (ok ? 0 : OOB));
+      if constexpr (PROJ == 1) {
+        const bool okp = is_proj & (e.y > -(1 << 19));
+        const float4 u = bload(rsxs, (e.w + qc * 4) | (okp ? 0 : OOB));
+        v.x += u.x, v.y += u.y, v.z += u.z, v.w += u.w;  // one of the two is all zeros
       }
-      rx[set][i] = v;
     }
+    rx[set][i] = v;
+  };
+  auto gload = [&](int s, int set) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) gload_d(s, set, i);
+    tread(s);
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) gload_x(set, i);
   };
 
+  auto lstore_d = [&](int buf, int set, int i) {
+    *reinterpret_cast<float4 *>(&Ds[buf][rowp + RP * i][chp * 4]) = rd[set][i];
+    bsum.x += bsel * rd[set][i].x, bsum.y += bsel * rd[set][i].y, bsum.z += bsel * rd[set][i].z,
+        bsum.w += bsel * rd[set][i].w;
+  };
+  auto lstore_x = [&](int buf, int set, int i) {
+    *reinterpret_cast<float4 *>(&Xs[buf][rowq + RQ * i][chq * 4]) = rx[set][i];
+  };
   auto lstore = [&](int buf, int set) {
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      *reinterpret_cast<float4 *>(&Ds[buf][rowp + RP * i][chp * 4]) = rd[set][i];
-      bsum.x += bsel * rd[set][i].x, bsum.y += bsel * rd[set][i].y, bsum.z += bsel * rd[set][i].z,
-          bsum.w += bsel * rd[set][i].w;
-    }
+    for (int i = 0; i < NP; ++i) lstore_d(buf, set, i);
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) *reinterpret_cast<float4 *>(&Xs[buf][rowq + RQ * i][chq * 4]) = rx[set][i];
+    for (int i = 0; i < NQ; ++i) lstore_x(buf, set, i);
   };
 
   floatx16 acc[PT][QT];
@@ -216,37 +229,49 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
 
   // ---- software pipeline: step s uses LDS buffer s&1 ----
   //   sub-steps 0..NSS-2: fragment reads of sub-step ss+1 ride on the MFMAs of sub-step ss; the
-  //     address arithmetic and buffer loads of step s+2 are spread over the first sub-steps, the
-  //     LDS writes of step s+1 (loaded one step ago) over the later ones;
+  //     address arithmetic and buffer loads of step s+2 are spread over the first four sub-steps,
+  //     the LDS writes of step s+1 (loaded one step ago) over the next three;
   //   barrier; first fragments of step s+1; MFMAs of the last sub-step.
+  // Every sub-step is closed by a scheduling fence: without it the compiler moves fragment reads
+  // between sub-steps and some end up right in front of the MFMA that needs them.
   constexpr int NM = 2 * PT * QT;  // MFMAs per sub-step
-  constexpr int NV = NP + NQ * (PROJ == 1 ? 2 : 1);  // buffer loads per step
-  constexpr int NW = NP + NQ;                   // LDS writes per step
+  constexpr int NW = NP + NQ;      // staged rows per thread and step (buffer loads, LDS writes)
+  constexpr int LPS = (NW + 3) / 4;  // rows loaded per sub-step over sub-steps 0..3
+  constexpr int WPS = (NW + 2) / 3;  // rows written per sub-step over sub-steps 4..6
+  static_assert(NSS == 8, "placement of loads and writes");
   auto step = [&](int s, auto par_tag) {
     constexpr int par = decltype(par_tag)::value;
-    gload(s + 2, par);  // set `par` held step s, already in LDS
-    rt_make(s + 3);     // other table buffer than the one gload(s + 2) reads
 #pragma unroll
     for (int ss = 0; ss + 1 < NSS; ++ss) {
       lfrag(par, ss + 1, (ss + 1) & 1);
       mma(ss & 1);
-    }
-    lstore(par ^ 1, par ^ 1);  // step s+1
-    {
-      constexpr int LPS = (NV + 3) / 4;  // loads per sub-step over sub-steps 0..3
-      constexpr int WPS = (NW + 2) / 3;  // writes per sub-step over sub-steps 4..6
+      if (ss == 0) {
+        tread(s + 2);     // table entries a sub-step or more ahead of the loads that need them
+        rt_make(s + 3);   // the other table buffer
+      }
+      if (ss < 4) {                 // step s + 2 into set `par`, which held step s, already in LDS
 #pragma unroll
-      for (int ss = 0; ss + 1 < NSS; ++ss) {
+        for (int it = ss * LPS; it < (ss + 1) * LPS && it < NW; ++it) {
+          if (it < NP) gload_d(s + 2, par, it);
+          else gload_x(par, it - NP);
+        }
+      } else {                      // step s + 1
 #pragma unroll
-        for (int i = 0; i < NM; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // one MFMA
-          if (i < 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // + fragment reads
-          if (ss < 4) __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);             // + address VALU
-          if (ss < 4 && i < LPS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // + a buffer load
-          if (ss >= 4 && i < WPS) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0); // + an LDS write
-          if (ss >= 4) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+        for (int it = (ss - 4) * WPS; it < (ss - 3) * WPS && it < NW; ++it) {
+          if (it < NP) lstore_d(par ^ 1, par ^ 1, it);
+          else lstore_x(par ^ 1, par ^ 1, it - NP);
         }
       }
+#pragma unroll
+      for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // one MFMA
+        if (i < 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // + fragment reads
+        if (ss < 4) __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);             // + address VALU
+        if (ss < 4 && i < 2 * LPS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // + a buffer load
+        if (ss >= 4 && i < WPS) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0); // + an LDS write
+        if (ss >= 4) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
     lfrag(par ^ 1, 0, 0);
