@@ -446,21 +446,19 @@ def main():
                                         perms[k], bl, bws, stream=main_s, prefetch_stream=pf)
                 main_s.synchronize()
                 tot[mode] += (time.perf_counter() - t0) * 1e3 / nb / 2
-            # the same pass captured once in a HIP graph and replayed (an extra figure: a failure to
-            # capture must not cost the benchmark line)
+            # the same pass captured once by the library in a HIP graph (nf_block_graph_create) and
+            # launched twice (an extra figure: a failure to capture must not cost the benchmark line)
             if tot["graph"] is not None:
                 try:
-                    graph = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(graph):
-                        nf.nf_block_train_epoch(blk, cfg.lr, cfg.momentum, b.batch, nb * b.batch, caches[k],
-                                                clabels[k], N, perms[k], bl, bws)
+                    graph = nf.nf_block_graph_create(blk, cfg.lr, cfg.momentum, b.batch, nb * b.batch, caches[k],
+                                                     clabels[k], N, perms[k], bl, bws)
                     torch.cuda.synchronize()
                     for _ in range(2):
                         t0 = time.perf_counter()
-                        graph.replay()
-                        torch.cuda.synchronize()
+                        nf.nf_block_graph_launch(graph, stream=main_s)
+                        main_s.synchronize()
                         tot["graph"] += (time.perf_counter() - t0) * 1e3 / nb / 2
-                    del graph
+                    nf.nf_block_graph_destroy(graph)
                 except Exception as exc:  # noqa: BLE001
                     log(f"[block] HIP-graph capture not available: {exc}")
                     tot["graph"] = None

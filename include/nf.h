@@ -26,10 +26,11 @@
  * ---- Ownership, streams, errors -----------------------------------------------------------
  *   The caller owns every buffer, including the workspace `ws` (size from
  *   nf_workspace_bytes, 256-byte aligned).  The library allocates nothing and keeps no
- *   state between calls (four documented exceptions: the static scratch array of
+ *   state between calls (five documented exceptions: the static scratch array of
  *   nf_local_step_static, the event pool of the prefetch mode of nf_block_train_epoch, the
- *   process-wide contraction mode of nf_contraction, and the measurement aid nf_prof_begin/end).  `stream` is a hipStream_t passed as void* (NULL = default
- *   stream); every call only enqueues work on it and never synchronises the host.
+ *   graph handles of nf_block_graph_create, the process-wide contraction mode of nf_contraction,
+ *   and the measurement aid nf_prof_begin/end).  `stream` is a hipStream_t passed as void*
+ *   (NULL = default stream); every call only enqueues work on it and never synchronises the host.
  *   Every device pointer must be 16-byte aligned.
  *   Every call returns NF_OK (0) or a negative nf_status.  Arguments are validated before
  *   anything is enqueued, so a failing call has no side effects on device memory.
@@ -253,6 +254,30 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
                              const float *cache, const int32_t *cache_labels, int64_t capacity,
                              const int64_t *idx, float *losses, void *ws, size_t ws_bytes,
                              void *stream, void *prefetch_stream);
+
+/* The same pass (Algorithm 2, the Worker's loop over the batches of a block) as a HIP graph the
+ * library captures itself (the per-batch work of a block is a few
+ * hundred short launches; replayed from a graph they are enqueued by one call and the gaps between
+ * them shrink).  nf_block_graph_create takes the arguments of nf_block_train_epoch without the
+ * streams, validates them the same way (same error codes, nothing captured on error), captures the
+ * whole pass over the n_items samples on a private stream and instantiates it; *out is the handle.
+ * The graph is a snapshot of the ARGUMENTS: every pointer, B, n_items, lr, momentum, the descriptors
+ * and the contraction mode in force at creation are fixed; what the pointers point at (cache rows,
+ * the index list idx, weights, momentum) is read when the graph runs, so an epoch with a new shuffle
+ * is: rewrite idx on the device, launch again.  All buffers must stay alive until the handle is
+ * destroyed.  nf_block_graph_launch enqueues one pass on `stream` (default priority) of the device
+ * the graph was created on (another current device: NF_ERR_BAD_DESC); results are bit-identical to
+ * nf_block_train_epoch with prefetch_stream == NULL.  Launches of one handle must not overlap in
+ * time (they share ws).  nf_block_graph_destroy frees the handle (NULL is accepted).  Creation
+ * between nf_prof_begin and nf_prof_end is refused with NF_ERR_UNSUPPORTED.  These three calls are
+ * the only ones in the library that allocate: the graph objects and the handle, host side. */
+typedef struct nf_block_graph nf_block_graph;
+int32_t nf_block_graph_create(const nf_block *blk, const nf_sgd_desc *s, int32_t B, int64_t n_items,
+                              const float *cache, const int32_t *cache_labels, int64_t capacity,
+                              const int64_t *idx, float *losses, void *ws, size_t ws_bytes,
+                              nf_block_graph **out);
+int32_t nf_block_graph_launch(nf_block_graph *g, void *stream);
+int32_t nf_block_graph_destroy(nf_block_graph *g);
 
 /* After the block is trained: forward-only sweep with its final weights over rows [0, n_items)
  * of its input cache in batches of B (last one partial), writing the last layer's emitted

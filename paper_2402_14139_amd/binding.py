@@ -25,7 +25,8 @@ EXPORTS = ("nf_strerror", "nf_layer_out_dims", "nf_workspace_bytes", "nf_layer_f
            "nf_prof_begin", "nf_prof_end", "nf_workspace_region", "nf_block_workspace_bytes",
            "nf_block_train_epoch", "nf_block_fill_cache", "nf_layer_step_bytes", "nf_fit_linear",
            "nf_profile_layer", "nf_partition", "nf_aux_predict", "nf_block_evaluate", "nf_select_exit",
-           "nf_device_info", "nf_local_step_static", "nf_contraction")
+           "nf_device_info", "nf_local_step_static", "nf_contraction", "nf_block_graph_create",
+           "nf_block_graph_launch", "nf_block_graph_destroy")
 
 NF_WS_AUX_ACT, NF_WS_POOL_ARG, NF_WS_HEAD_ARG = 0, 1, 2
 NF_HEAD_POOL_AVG, NF_HEAD_POOL_MAX = 0, 1
@@ -128,6 +129,11 @@ def lib():
         L.nf_block_train_epoch.argtypes = [C.POINTER(Block), C.POINTER(SgdDesc), C.c_int32, C.c_int64, C.c_void_p,
                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                            C.c_void_p, C.c_void_p]
+        L.nf_block_graph_create.argtypes = [C.POINTER(Block), C.POINTER(SgdDesc), C.c_int32, C.c_int64, C.c_void_p,
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                            C.POINTER(C.c_void_p)]
+        L.nf_block_graph_launch.argtypes = [C.c_void_p, C.c_void_p]
+        L.nf_block_graph_destroy.argtypes = [C.c_void_p]
         L.nf_block_fill_cache.argtypes = [C.POINTER(Block), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nf_aux_predict.argtypes = [C.POINTER(LayerDesc), C.POINTER(AuxDesc), C.c_int32, C.c_void_p, C.c_void_p,
@@ -323,6 +329,24 @@ def nf_block_train_epoch(blk: Block, lr, momentum, B, n_items, cache, cache_labe
                                       _ptr(idx), _ptr(losses), wp, wn, _stream(stream),
                                       None if prefetch_stream is None else _stream(prefetch_stream)),
            "nf_block_train_epoch")
+
+
+def nf_block_graph_create(blk: Block, lr, momentum, B, n_items, cache, cache_labels, capacity, idx, losses, ws):
+    """Returns the handle (an integer address) of the captured block pass."""
+    s = SgdDesc(lr, momentum)
+    wp, wn = _ws(ws)
+    h = C.c_void_p()
+    _check(lib().nf_block_graph_create(C.byref(blk), C.byref(s), B, n_items, _ptr(cache), _ptr(cache_labels), capacity,
+                                       _ptr(idx), _ptr(losses), wp, wn, C.byref(h)), "nf_block_graph_create")
+    return h.value
+
+
+def nf_block_graph_launch(handle, stream=None):
+    _check(lib().nf_block_graph_launch(C.c_void_p(handle), _stream(stream)), "nf_block_graph_launch")
+
+
+def nf_block_graph_destroy(handle):
+    _check(lib().nf_block_graph_destroy(C.c_void_p(handle) if handle else None), "nf_block_graph_destroy")
 
 
 def nf_block_fill_cache(blk: Block, B, n_items, cache_in, labels_in, capacity_in, cache_out, labels_out,

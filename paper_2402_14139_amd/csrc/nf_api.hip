@@ -620,6 +620,8 @@ int32_t local_step_impl(const nf_layer_desc *d, const nf_aux_desc *a, const nf_s
 }
 
 }  // namespace
+
+bool prof_active() { return g_prof.on; }
 }  // namespace nf
 
 using namespace nf;

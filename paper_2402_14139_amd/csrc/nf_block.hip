@@ -13,6 +13,16 @@
 
 #include "../../include/nf.h"
 
+namespace nf {
+bool prof_active();  // nf_api.hip: true between nf_prof_begin and nf_prof_end
+}
+
+// One captured block pass (nf_block_graph_create): the instantiated graph and the device it lives on.
+struct nf_block_graph {
+  hipGraphExec_t exec;
+  int device;
+};
+
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -226,6 +236,56 @@ int32_t nf_block_train_epoch(const nf_block *blk, const nf_sgd_desc *s, int32_t 
     if (pf && j + 2 < n_batches && hipEventRecord(ev.done[slot], st) != hipSuccess) return fail(NF_ERR_DEVICE);
   }
   return NF_OK;
+}
+
+int32_t nf_block_graph_create(const nf_block *blk, const nf_sgd_desc *s, int32_t B, int64_t n_items,
+                              const float *cache, const int32_t *cache_labels, int64_t capacity,
+                              const int64_t *idx, float *losses, void *ws, size_t ws_bytes, nf_block_graph **out) {
+  if (!out) return NF_ERR_NULL;
+  *out = nullptr;
+  // event pairs around every launch cannot be part of a graph
+  if (nf::prof_active()) return NF_ERR_UNSUPPORTED;
+  int dev = 0;
+  NF_HIP(hipGetDevice(&dev));
+  // a stream of its own for the capture (default priority), gone again before the call returns
+  hipStream_t cs = nullptr;
+  NF_HIP(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+  if (hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+    (void)hipStreamDestroy(cs);
+    return NF_ERR_DEVICE;
+  }
+  // validation happens in here, before the first enqueue: an argument error leaves an empty capture
+  const int32_t rc = nf_block_train_epoch(blk, s, B, n_items, cache, cache_labels, capacity, idx, losses, ws, ws_bytes,
+                                          cs, nullptr);
+  hipGraph_t graph = nullptr;
+  const hipError_t ec = hipStreamEndCapture(cs, &graph);  // always: a stream must not be left capturing
+  (void)hipStreamDestroy(cs);
+  if (rc != NF_OK || ec != hipSuccess || !graph) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc != NF_OK ? rc : NF_ERR_DEVICE;
+  }
+  hipGraphExec_t exec = nullptr;
+  const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (ei != hipSuccess || !exec) return NF_ERR_DEVICE;
+  *out = new nf_block_graph{exec, dev};
+  return NF_OK;
+}
+
+int32_t nf_block_graph_launch(nf_block_graph *g, void *stream) {
+  if (!g) return NF_ERR_NULL;
+  int dev = 0;
+  NF_HIP(hipGetDevice(&dev));
+  if (dev != g->device) return NF_ERR_BAD_DESC;
+  NF_HIP(hipGraphLaunch(g->exec, static_cast<hipStream_t>(stream)));
+  return NF_OK;
+}
+
+int32_t nf_block_graph_destroy(nf_block_graph *g) {
+  if (!g) return NF_OK;
+  const hipError_t e = hipGraphExecDestroy(g->exec);
+  delete g;
+  return e == hipSuccess ? NF_OK : NF_ERR_DEVICE;
 }
 
 int32_t nf_block_fill_cache(const nf_block *blk, int32_t B, int64_t n_items, const float *cache_in,

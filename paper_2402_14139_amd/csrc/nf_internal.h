@@ -62,6 +62,8 @@ hipError_t launch_igemm_fwd_fast(const FwdProblem &p, hipStream_t st, const char
 
 // current contraction mode (nf_contraction): NF_CONTRACT_F32, NF_CONTRACT_BF16X6 or NF_CONTRACT_BF16X9
 int contraction_mode();
+// true between nf_prof_begin and nf_prof_end (every launch is then bracketed by a pair of events)
+bool prof_active();
 // fp32 contraction on the bf16 matrix cores through three-way split operands (igemm_fwd_split.hip);
 // launch_igemm_fwd_fast hands over to it in the NF_CONTRACT_BF16X* modes when applicable (nine: all
 // nine piece products instead of six)

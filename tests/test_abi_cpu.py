@@ -393,3 +393,11 @@ def test_contraction_mode_switch():
         assert nf.nf_contraction() == nf.NF_CONTRACT_F32
     finally:
         nf.nf_contraction(prev)
+
+
+def test_block_graph_handles_without_a_device():
+    """The graph entry points' argument checks that need no GPU."""
+    L = nf.lib()
+    assert L.nf_block_graph_create(None, None, 1, 1, None, None, 1, None, None, None, 0, None) == nf.NF_ERR_NULL
+    assert L.nf_block_graph_launch(None, None) == nf.NF_ERR_NULL
+    assert L.nf_block_graph_destroy(None) == nf.NF_OK

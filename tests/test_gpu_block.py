@@ -357,3 +357,66 @@ def test_block_epoch_under_graph_capture():
         want_state, want_loss = eager_states[r]
         assert torch.equal(gl, want_loss), f"losses differ after replay {r}"
         assert all(torch.equal(a, b) for a, b in zip(cap.state(), want_state)), f"state differs after replay {r}"
+
+
+def test_block_graph_captured_by_the_library():
+    """nf_block_graph_create / launch / destroy: the library captures the block pass itself.  Three
+    launches (with eager work and synchronisations in between, on a stream of the caller) leave
+    bit-for-bit the state that three eager calls leave, checked after every launch; a new shuffle
+    written into the same index buffer is picked up by the next launch; argument errors come back
+    as from nf_block_train_epoch and leave no handle."""
+    specs, skip = _small_block("proj")
+    cls, N, B, lr, mu = 10, 12, 6, 0.02, 0.9
+    X, lab, idx, params = _gen(specs, cls, N, seed=25)
+    cache = G.to_dev(layout.act_to_lib(X).reshape(N, -1))
+    clab = G.to_dev(lab)
+    idx2 = np.ascontiguousarray(idx[::-1])
+    nb = N // B
+    eager = GpuBlock(specs, skip, cls, params, B, True)
+    el = torch.zeros((nb, len(specs)), device="cuda")
+    eidx = G.to_dev(idx)
+    eager_states = []
+    for r in range(3):
+        if r == 2:
+            eidx.copy_(torch.from_numpy(idx2))
+        nf.nf_block_train_epoch(eager.blk, lr, mu, B, N, cache, clab, N, eidx, el, eager.ws)
+        torch.cuda.synchronize()
+        eager_states.append(([s.clone() for s in eager.state()], el.clone()))
+    cap = GpuBlock(specs, skip, cls, params, B, True)
+    gl = torch.zeros((nb, len(specs)), device="cuda")
+    gidx = G.to_dev(idx)
+    torch.cuda.synchronize()
+    # a workspace that is too small: the error of nf_block_train_epoch, and no handle
+    with pytest.raises(nf.NfError) as e:
+        nf.nf_block_graph_create(cap.blk, lr, mu, B, N, cache, clab, N, gidx, gl, cap.ws[:256])
+    assert e.value.status == nf.NF_ERR_WORKSPACE
+    # refused while the per-launch event timing is on
+    nf.nf_prof_begin()
+    try:
+        with pytest.raises(nf.NfError) as e:
+            nf.nf_block_graph_create(cap.blk, lr, mu, B, N, cache, clab, N, gidx, gl, cap.ws)
+        assert e.value.status == nf.NF_ERR_UNSUPPORTED
+    finally:
+        nf.nf_prof_end()
+    print("create", flush=True)
+    g = nf.nf_block_graph_create(cap.blk, lr, mu, B, N, cache, clab, N, gidx, gl, cap.ws)
+    torch.cuda.synchronize()
+    # creating the graph ran nothing
+    assert all(torch.equal(a, b) for a, b in zip(cap.state(), GpuBlock(specs, skip, cls, params, B, True).state()))
+    stream = torch.cuda.Stream()
+    scratch = torch.zeros(1 << 16, device="cuda")
+    try:
+        for r in range(3):
+            if r == 2:
+                gidx.copy_(torch.from_numpy(idx2))
+                torch.cuda.synchronize()
+            print(f"launch {r}", flush=True)
+            nf.nf_block_graph_launch(g, stream=stream)
+            stream.synchronize()
+            scratch.add_(1.0).sum().item()      # eager work and a synchronisation between launches
+            torch.cuda.synchronize()
+            want_state, want_loss = eager_states[r]
+            assert torch.equal(gl, want_loss), f"losses differ after launch {r}"
+            assert all(torch.equal(a, b) for a, b in zip(cap.state(), want_state)), f"state differs after launch {r}"
+    finally:
+        nf.nf_block_graph_destroy(g)
