@@ -76,7 +76,11 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   constexpr bool PROJ = MODE == 1, EPI = MODE == 2;
   using MM = Mfma<MF>;
   using acc_t = typename MM::acc_t;
-  constexpr int LDK = BK + 4;        // +4 floats: 16-byte row reads of consecutive rows hit distinct banks
+  // Row padding that keeps the 16-byte fragment reads free of bank conflicts (counted with
+  // SQ_LDS_BANK_CONFLICT on a read-only loop): a wave reading 32 consecutive rows (32x32x2 fragments)
+  // needs a row stride of 4 mod 32 floats, one reading 16 consecutive rows in four k groups
+  // (16x16x4 fragments) a stride of 8 mod 16; the other choice doubles the LDS time of every read.
+  constexpr int LDK = BK + (MF == 16 ? 8 : 4);
   constexpr int NTHREADS = WM * WN * 64;
   constexpr int CPR = BK / 4;        // 16-byte chunks per staged row
   constexpr int RPP = NTHREADS / CPR;  // rows staged per pass
