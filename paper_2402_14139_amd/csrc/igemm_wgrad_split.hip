@@ -70,7 +70,7 @@ template <bool PROJ, int NP>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void igemm_wgrad_split_kernel(WgradProblem p) {
   constexpr int BP = 128, BQ = 128;
   constexpr int MT = 2, NT = 2;  // 32x32 MFMA tiles per wave: 64x64
-  constexpr int LDH = BKM;       // bf16 per LDS row: 64 bytes, quarter stored at quarter ^ ((row / 4) % 4)
+  constexpr int LDH = BKM;       // bf16 per LDS row: 64 bytes, quarter q stored at q ^ f(row), see the staging task
 
   // [operand: d, x][group][piece][LDS row][m]: 96 KiB (one array, addressed as such: LDS reached
   // through a converted pointer keeps the compiler from holding the per-thread arrays in registers)
@@ -100,12 +100,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // ---- staging task of this thread: 8 reduction rows (mg) x 4 columns (pc) of one operand ----
   const int ts = t & 255;
   const bool is_x = w4 >= 2;  // uniform per wave
-  // (lanes along the columns: 512 contiguous bytes per row and load instruction.  The LDS writes of
-  // this mapping have some bank conflicts; with 4 consecutive lanes on the 4 row groups instead they
-  // have none, but the loads then touch 4 rows per 16 lanes and the kernel is 6 % slower)
+  // (lanes along the columns: 512 contiguous bytes per row and load instruction)
+  // Swizzle of the four 16-byte quarters of an LDS row, f(row) = ((row >> 1) ^ (row >> 2)) & 3: the
+  // writes below go out 8 lanes = 8 consecutive rows at a time into a 128-byte window of banks and
+  // want f distinct over rows of equal parity; the fragment reads go 16 consecutive rows at a time
+  // into 256 bytes and want f distinct over rows that are equal mod 4.  This f gives both (counted
+  // with SQ_LDS_BANK_CONFLICT per access pattern; (row >> 2) & 3 alone leaves the writes 2-way
+  // conflicted, (row >> 1) & 3 alone the reads).
   const int u = ts & 127, pc = u % 32, mg = u / 32;
   const int wrow = pc;                                   // + 32 * (column within the chunk)
-  const int wcol = (mg ^ ((pc >> 2) & 3)) << 3;          // swizzled LDS column of the 8 rows
+  const int wcol = (mg ^ (((pc >> 1) ^ (pc >> 2)) & 3)) << 3;  // swizzled LDS column of the 8 rows
   // d: columns p0 + pc*4 .. +3
   const int pcol = p0 + pc * 4;
   const int dcol_off = pcol < p.P ? pcol * 4 : OOB;
@@ -223,7 +227,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // a slab: piece r / (MT + NT), then the d tiles, then the x tiles
   uint4 af[2][3][MT], bfr[2][3][NT];
   constexpr int NR = 3 * (MT + NT);
-  const int rcol[2] = {((g ^ ((j >> 2) & 3)) << 3), (((2 + g) ^ ((j >> 2) & 3)) << 3)};  // swizzled column per slab
+  const int fsw = ((j >> 1) ^ (j >> 2)) & 3;
+  const int rcol[2] = {((g ^ fsw) << 3), (((2 + g) ^ fsw) << 3)};  // swizzled column per slab
   auto lfrag1 = [&](int ks, int slot, int r) {
     const int pcs = r / (MT + NT), i = r % (MT + NT);
     if (i < MT)
