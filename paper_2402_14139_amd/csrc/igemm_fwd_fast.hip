@@ -17,10 +17,6 @@
 
 #include "nf_internal.h"
 
-#ifndef NF_FWD_FENCE
-#define NF_FWD_FENCE 1
-#endif
-
 namespace nf {
 namespace {
 
@@ -249,38 +245,25 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   auto step = [&](int kb, auto par_tag) {
     constexpr int par = decltype(par_tag)::value;
     gload(kb + 2, par);  // set `par` held step kb, already in LDS
+    static_assert(!SCHED || NKS > 2, "placement of loads and writes");
 #pragma unroll
     for (int ks = 0; ks + 1 < NKS; ++ks) {
       lfrag(par, ks + 1, (ks + 1) & 1);
       mma(ks & 1);
-      if constexpr (NF_FWD_FENCE && SCHED && NKS > 2) {
-        if (ks + 2 == NKS) lstore(par ^ 1, par ^ 1);
-#pragma unroll
-        for (int i = 0; i < NM; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-          if (ks == 1 && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-          if (ks + 2 == NKS && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-          if (ks != 0) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);  // fragment reads stay in the sub-step they were written in
-      }
-    }
-    if constexpr (!(NF_FWD_FENCE && SCHED && NKS > 2)) lstore(par ^ 1, par ^ 1);  // step kb+1
-    if constexpr (SCHED && !(NF_FWD_FENCE && NKS > 2)) {
-#pragma unroll
-      for (int ks = 0; ks + 1 < NKS; ++ks) {
-        const bool first = ks == 0, last = ks + 2 == NKS;
+      if (ks + 2 == NKS) lstore(par ^ 1, par ^ 1);  // step kb+1
+      if constexpr (SCHED) {
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // one MFMA
           if (i < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // + a fragment read
-          if (first) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);           // + address VALU
-          if ((NKS == 2 || ks == 1) && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-          if (last && NKS > 2 && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-          if (!first) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+          if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);         // + address VALU
+          if (ks == 1 && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);         // + a buffer load
+          if (ks + 2 == NKS && i >= NR && i < NR + NV) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // + an LDS write
+          if (ks != 0) __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
         }
+        // Fragment reads stay in the sub-step they were written in: without this fence the compiler
+        // moved some of them right in front of the MFMA that needs them.
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     __syncthreads();
