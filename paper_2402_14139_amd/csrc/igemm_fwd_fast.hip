@@ -298,13 +298,15 @@ __global__ __launch_bounds__(WM *WN * 64) void igemm_fwd_fast_kernel(FwdProblem 
   gload(kb0 + 1, 1);
   __syncthreads();
   lfrag(0, 0, 0);
-  // Steps go in pairs with no branch between them (an odd count runs one step of zeros: loads past
-  // kb_end return zeros).  A conditional second step makes the compiler copy every accumulator
-  // out of and back into the MFMA register file at the loop head, behind a wait for all loads.
-  for (int kb = kb0; kb < kb_end; kb += 2) {
+  // Inside the loop the steps go in pairs with no branch between them: a conditional second step
+  // there makes the compiler copy every accumulator out of and back into the MFMA register file at
+  // the loop head, behind a wait for all loads.  The last step of an odd count follows the loop.
+  int kb = kb0;
+  for (; kb + 1 < kb_end; kb += 2) {
     step(kb, std::integral_constant<int, 0>{});
     step(kb + 1, std::integral_constant<int, 1>{});
   }
+  if ((kb_end - kb0) & 1) step(kb, std::integral_constant<int, 0>{});  // odd count: the last step, after the loop
 
   // ---- split reduction: raw partial sums, slice blockIdx.y of out[splits][M][N] ----
   if (gridDim.y > 1) {

@@ -294,11 +294,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void igemm_wgrad_fast_kernel(WgradProb
   rt_make(2);
   __syncthreads();
   lfrag(0, 0, 0);
-  // unconditional pairs: an odd count runs one step of zeros (rows past m_end load zeros)
-  for (int s = 0; s < nsteps; s += 2) {
+  // unconditional pairs inside the loop (a conditional second step there makes the compiler move the
+  // accumulators out of and back into the MFMA register file around every iteration); an odd count
+  // ends with one step after the loop
+  int s = 0;
+  for (; s + 1 < nsteps; s += 2) {
     step(s, std::integral_constant<int, 0>{});
     step(s + 1, std::integral_constant<int, 1>{});
   }
+  if (nsteps & 1) step(s, std::integral_constant<int, 0>{});
 
   // ---- store the partial tile: lane holds, per (a, e), QT consecutive q ----
   float *part = p.part + (long long)bz * p.P * p.Qld;

@@ -441,7 +441,7 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     g.d = dU, g.x = y, g.part = wsf(ws, w.part_aux), g.part_b = wsf(ws, w.part_b_aux);
     g.Qld = w.Qld_aux;
     g.splits = w.splits_aux;
-    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
+    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;  // whole 32-row steps
     g.div_howo = FastDiv(ad.Hu * ad.Wu), g.div_wo = FastDiv(ad.Wu);
     const int32_t rc = enqueue_wgrad(g, st);
     if (rc) return rc;
@@ -476,7 +476,7 @@ int32_t run_bwd(const nf_layer_desc *d, const LayerDims &ld, const nf_aux_desc *
     if (d->skip_kind == 2) g.xs = xs, g.Cs = d->skip_C, g.Hs = d->skip_H, g.Ws = d->skip_W, g.ss = d->skip_stride;
     g.P = d->C_out, g.M = B * ld.Ho * ld.Wo, g.RSC = d->R * d->S * d->C_in, g.Q = g.RSC + g.Cs, g.Qld = w.Qld_layer;
     g.splits = w.splits_layer;
-    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 63) / 64 * 64;  // whole pairs of 32-row steps
+    g.m_per_split = ((g.M + g.splits - 1) / g.splits + 31) / 32 * 32;  // whole 32-row steps
     g.div_howo = FastDiv(ld.Ho * ld.Wo), g.div_wo = FastDiv(ld.Wo);
     const int32_t rc = enqueue_wgrad(g, st);
     if (rc) return rc;
