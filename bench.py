@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 # scaled by what the same counter reads for a plain 1 GiB copy (`--traffic-calib`): FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0.  Averages over the launches of one step; summary under profiles/.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("cfg3_resnet18", "igemm_wgrad_fast_128x128"): 66.5e6 + 37.9e6,
-    ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 67.5e6 + 16.8e6,
+    ("cfg3_resnet18", "igemm_wgrad_fast_128x128"): 66.7e6 + 37.9e6,
+    ("cfg3_resnet18", "igemm_fwd_fast_128x128"): 67.6e6 + 16.8e6,
 }
 TRAFFIC_SOURCE = ("offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this script, scaled by a 1 GiB copy "
                   "(FETCH x 2.0, WRITE x 1.0); summary in profiles/local_step_cfg3_hbm_traffic.md; not re-measured "
@@ -45,11 +45,11 @@ TRAFFIC_SOURCE = ("offline: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over 
 # live below) add about 3 us to every launch, which halves the apparent rate of a 6 us copy.
 HBM_OFFLINE = {
     "cfg3_resnet18": [
-        ("cache_copy_kernel", 1048576, 33.59e6, 6.30), ("cache_copy_kernel", 2097152, 67.15e6, 14.92),
-        ("wgrad_reduce_kernel", 325376, 17.62e6, 7.28), ("wgrad_reduce_kernel", 1283584, 50.11e6, 15.26),
-        ("wgrad_reduce_kernel", 402944, 76.87e6, 17.49), ("wgrad_reduce_kernel", 697856, 141.74e6, 25.75),
-        ("head_wide_kernel<4>", 215040, 22.45e6, 17.60), ("head_wide_kernel<4>", 149504, 6.45e6, 10.60),
-        ("head_sample_kernel<4, false>", 83968, 4.34e6, 12.62),
+        ("cache_copy_kernel", 1048576, 33.59e6, 6.41), ("cache_copy_kernel", 2097152, 67.15e6, 14.84),
+        ("wgrad_reduce_kernel", 325376, 17.62e6, 7.39), ("wgrad_reduce_kernel", 1283584, 50.11e6, 15.29),
+        ("wgrad_reduce_kernel", 402944, 76.87e6, 17.70), ("wgrad_reduce_kernel", 697856, 141.74e6, 25.85),
+        ("head_wide_kernel<4>", 215040, 22.45e6, 17.78), ("head_wide_kernel<4>", 149504, 6.45e6, 10.78),
+        ("head_sample_kernel<4, false>", 83968, 4.34e6, 12.78),
     ],
 }
 HBM_OFFLINE_SOURCE = "profiles/local_step_cfg3_hbm_traffic.md (offline rocprofv3 passes; not re-measured by this run)"
