@@ -1,4 +1,4 @@
-"""CPU checks of the arithmetic behind the NF_CONTRACT_BF16X6 mode (no GPU, no library code):
+"""CPU checks of the arithmetic behind the NF_CONTRACT_BF16X6 / NF_CONTRACT_BF16X9 modes (no GPU, no library code):
 the three-way split of an fp32 number into bfloat16 pieces as the kernels do it (truncation to the
 top 16 bits, remainders in fp32), written out in numpy.
 
@@ -6,6 +6,7 @@ top 16 bits, remainders in fp32), written out in numpy.
 * each of the nine piece products is exact in fp32;
 * the pieces fall off by at least 2^-7 and 2^-15 of |x|, so the three products the kernels leave out
   (m*l, l*m, l*l) are together below 2^-21 of |x*w| in the worst case (about 2^-24 in the root mean square);
+* all nine piece products together ARE the product x*w, exactly (the nine-product mode);
 * a dot product from the six kept products, with the fp32 accumulator rounded once per MFMA (16
   reduction indices), is as close to the fp64 result as the same dot product with the accumulator
   rounded once per fp32 MFMA (2 reduction indices).
@@ -83,3 +84,19 @@ def test_six_product_dot_is_as_close_as_fp32():
         errs32.append(abs(float(acc32) - ref))
     rms6, rms32 = np.sqrt(np.mean(np.square(errs6))), np.sqrt(np.mean(np.square(errs32)))
     assert rms6 <= 2.0 * rms32 + 1e-9, (rms6, rms32)
+
+
+def test_nine_piece_products_are_the_product():
+    """NF_CONTRACT_BF16X9: nothing is left out, so what enters the fp32 accumulation for one
+    multiply-add is x*w itself (each piece product is exact, and they sum to it exactly in fp64)."""
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(100000) * np.exp2(rng.integers(-12, 12, 100000))).astype(np.float32)
+    w = (rng.standard_normal(100000) * 0.05).astype(np.float32)
+    xs, ws = split3(x), split3(w)
+    total = np.zeros(x.shape, dtype=np.float64)
+    for a in xs:
+        for b in ws:
+            total += a.astype(np.float64) * b.astype(np.float64)
+    # fp64 holds every partial sum exactly here: all terms are multiples of the smallest product's
+    # unit and the sum spans fewer than 53 bits
+    assert np.array_equal(total, x.astype(np.float64) * w.astype(np.float64))
