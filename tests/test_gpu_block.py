@@ -420,3 +420,52 @@ def test_block_graph_captured_by_the_library():
             assert all(torch.equal(a, b) for a, b in zip(cap.state(), want_state)), f"state differs after launch {r}"
     finally:
         nf.nf_block_graph_destroy(g)
+
+
+def test_block_graph_keeps_the_contraction_mode_of_its_creation():
+    """A graph created in the split-operand mode runs the split kernels whatever the mode is when it
+    is launched, and the other way round (cfg3's 256-filter block at full size): each graph
+    reproduces, bit for bit, the eager pass made in the mode of its creation, and the two modes
+    differ from each other."""
+    cfg0 = workloads.config("cfg3")
+    k = 2
+    B = cfg0.blocks[k].batch
+    cfg, specs, skip, params = _cfg_block("cfg3", k, B, True)
+    N = B + B // 2
+    f = specs[0]
+    g = torch.Generator(device="cuda").manual_seed(7)
+    cache = torch.randn((N, f.H_in * f.W_in * f.C_in), device="cuda", generator=g).abs_()
+    clab = torch.randint(0, cfg.n_classes, (N,), device="cuda", generator=g, dtype=torch.int32)
+    idx = torch.randperm(N, device="cuda", generator=g)
+    lr, mu = 1e-3, 0.9
+    nb = (N + B - 1) // B
+    modes = (nf.NF_CONTRACT_F32, nf.NF_CONTRACT_BF16X6)
+    start = nf.nf_contraction()
+    eager, graphs = {}, {}
+    try:
+        for m in modes:
+            nf.nf_contraction(m)
+            gb = GpuBlock(specs, skip, cfg.n_classes, params, B, True)
+            losses = torch.zeros((nb, len(specs)), device="cuda")
+            nf.nf_block_train_epoch(gb.blk, lr, mu, B, N, cache, clab, N, idx, losses, gb.ws)
+            torch.cuda.synchronize()
+            eager[m] = (losses.clone(), [t.clone() for t in gb.state()])
+            del gb
+            cap = GpuBlock(specs, skip, cfg.n_classes, params, B, True)
+            gl = torch.zeros((nb, len(specs)), device="cuda")
+            graphs[m] = (nf.nf_block_graph_create(cap.blk, lr, mu, B, N, cache, clab, N, idx, gl, cap.ws), cap, gl)
+        # launch each graph with the OTHER mode in force
+        for m, other in zip(modes, modes[::-1]):
+            nf.nf_contraction(other)
+            h, cap, gl = graphs[m]
+            print(f"launch graph created in mode {m} under mode {other}", flush=True)
+            nf.nf_block_graph_launch(h)
+            torch.cuda.synchronize()
+            want_l, want_s = eager[m]
+            assert torch.equal(gl, want_l), m
+            assert all(torch.equal(a, b) for a, b in zip(cap.state(), want_s)), m
+        assert not all(torch.equal(a, b) for a, b in zip(eager[modes[0]][1], eager[modes[1]][1]))
+    finally:
+        nf.nf_contraction(start)
+        for h, _, _ in graphs.values():
+            nf.nf_block_graph_destroy(h)
